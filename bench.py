@@ -1,0 +1,274 @@
+#!/usr/bin/env python3
+"""Benchmark of the batched heterogeneous-adapter LoRA delta on one MI355X.
+
+A "step" is one layer call of the whole hot path over one synthetic batch: build segments,
+then shrink and expand of every projection (for MoE workloads the up/gate and the down
+application).  Weights, activations, ids and outputs are resident in HBM before the timed
+region.  The layer index rotates over several layers' worth of pool so that adapter weights
+come from HBM, not from the 256 MB last-level cache, as they do in layer-by-layer decoding.
+
+Prints one JSON line (see README for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="mixtral_moe_decode")
+    ap.add_argument("--layers", type=int, default=0, help="layers in the pool (0 = per-workload default)")
+    ap.add_argument("--seed", type=int, default=1234)
+    ap.add_argument("--hot", action="store_true", help="reuse one layer (weights warm in cache)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--all", action="store_true", help="also measure the other workloads (extra field)")
+    return ap.parse_args()
+
+
+DEFAULT_LAYERS = {"dense_small": 8, "llama8b_decode": 8, "prefill": 4, "mixtral_moe_decode": 8,
+                  "finegrained_moe_decode": 4, "mixtral_r64_microbench": 1}
+
+
+class Phase:
+    def __init__(self, name, fn, bytes_):
+        self.name, self.fn, self.bytes = name, fn, bytes_
+
+
+def make_phases(L, W, dp, db, run, acct):
+    """The launches of one step, each with the algorithmic bytes it must move."""
+    w = dp.workload
+    pool, seg = dp.pool, db.seg
+    S, P_act, T_act, r = acct["S"], acct["P_act"], acct["T_act"], w.rank
+    phases = [Phase("build_segments", lambda layer: run.build_segments(), 12 * db.P)]
+    if w.kind == "moe":
+        g, d = w.projs[0], w.projs[2]
+        x, mid = db.inputs["x"], db.inputs["mid"]
+        phases.append(Phase(
+            "upgate_shrink",
+            lambda layer: L.lora_moe_shrink(pool, layer, L.LORA_MOE_UPGATE, x, x.shape[1],
+                                            db.token_of_pair, seg, run.ws),
+            2 * S * r * g.h_in * 2 + T_act * g.h_in * 2))
+        phases.append(Phase(
+            "upgate_expand",
+            lambda layer: L.lora_moe_expand(pool, layer, L.LORA_MOE_UPGATE, seg, db.y["gate"],
+                                            db.y["up"], db.y["gate"].shape[1], run.ws),
+            2 * (S * r * g.h_out * 2 + P_act * g.h_out * 4)))
+        phases.append(Phase(
+            "down_shrink",
+            lambda layer: L.lora_moe_shrink(pool, layer, L.LORA_MOE_DOWN, mid, mid.shape[1], None,
+                                            seg, run.ws),
+            S * r * d.h_in * 2 + P_act * d.h_in * 2))
+        phases.append(Phase(
+            "down_expand",
+            lambda layer: L.lora_moe_expand(pool, layer, L.LORA_MOE_DOWN, seg, db.y["down"], None,
+                                            db.y["down"].shape[1], run.ws),
+            S * r * d.h_out * 2 + P_act * d.h_out * 4))
+    else:
+        seen = set()
+        for j, p in enumerate(w.projs):
+            x, y = db.inputs[p.input], db.y[p.name]
+            xb = 0 if p.input in seen else P_act * p.h_in * 2
+            seen.add(p.input)
+            phases.append(Phase(
+                f"{p.name}_shrink",
+                lambda layer, j=j, x=x: L.lora_shrink(pool, layer, j, x, x.shape[1], None, seg, run.v),
+                S * r * p.h_in * 2 + xb))
+            phases.append(Phase(
+                f"{p.name}_expand",
+                lambda layer, j=j, y=y: L.lora_expand(pool, layer, j, run.v, seg, y, y.shape[1],
+                                                      L.LORA_DTYPE_BF16),
+                S * r * p.h_out * 2 + P_act * p.h_out * 4))
+    return phases
+
+
+def measure(name, args, steps, warmup, with_cpu_baseline):
+    import numpy as np
+    import torch
+
+    import paper_2604_07173_amd as L
+    import workloads as W
+    from paper_2604_07173_amd.harness import DeviceBatch, DevicePool, LayerRunner
+
+    w = W.WORKLOADS[name]
+    n_layers = 1 if args.hot else (args.layers or DEFAULT_LAYERS.get(name, 4))
+    b = W.make_batch(w, args.seed, y_mode="normal")
+    ws = W.make_weights(w, args.seed, n_layers=n_layers)
+    dp = DevicePool(ws, b.scale)
+    db = DeviceBatch(b)
+    run = LayerRunner(dp, db)
+    acct = W.algorithmic_bytes(w, b.adapter_id, b.expert_id)
+    phases = make_phases(L, W, dp, db, run, acct)
+
+    def step(it):
+        layer = it % n_layers
+        for ph in phases:
+            ph.fn(layer)
+
+    # ---- whole-step throughput ----------------------------------------------------------
+    for it in range(warmup):
+        step(it)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for it in range(steps):
+        step(warmup + it)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / steps
+
+    # ---- per-launch durations with events on the launch stream ---------------------------
+    n_ev = min(steps, 100)
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(len(phases) + 1)] for _ in range(n_ev)]
+    for it in range(n_ev):
+        layer = it % n_layers
+        evs[it][0].record()
+        for k, ph in enumerate(phases):
+            ph.fn(layer)
+            evs[it][k + 1].record()
+    torch.cuda.synchronize()
+    per_phase = {}
+    for k, ph in enumerate(phases):
+        ts = np.array([evs[it][k].elapsed_time(evs[it][k + 1]) for it in range(n_ev)]) * 1e3  # us
+        per_phase[ph.name] = dict(us=float(np.mean(ts)), us_median=float(np.median(ts)),
+                                  bytes=int(ph.bytes),
+                                  gbs=float(ph.bytes / (np.mean(ts) * 1e-6) / 1e9))
+    dom = max(phases[1:], key=lambda ph: per_phase[ph.name]["us"])
+    d = per_phase[dom.name]
+    roofline = dict(bound="hbm", kernel=dom.name, achieved=round(d["gbs"], 1), peak=HBM_PEAK_GBS,
+                    unit="GB/s", frac=round(d["gbs"] / HBM_PEAK_GBS, 4),
+                    traffic=read_traffic(name, dom.name), us_per_launch=round(d["us"], 2),
+                    algorithmic_bytes=int(dom.bytes))
+
+    total_bytes = acct["total"]
+    res = dict(
+        workload=name, ms_per_step=ms_per_step, tokens_per_s=w.tokens / (ms_per_step * 1e-3),
+        pairs_per_s=w.pairs / (ms_per_step * 1e-3),
+        step_gbs=total_bytes / (ms_per_step * 1e-3) / 1e9,
+        step_frac_of_peak=total_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        algorithmic_bytes=int(total_bytes), segments=acct["S"], pairs=acct["P_act"],
+        layers_in_pool=n_layers, pool_gib=dp.nbytes / 2 ** 30, phases=per_phase, roofline=roofline)
+
+    if with_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(w, b, ws)
+    del dp, db, run
+    torch.cuda.empty_cache()
+    return res
+
+
+def read_traffic(workload, kernel):
+    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), if a summary
+    for this workload and kernel is on file under profiles/."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        parts = line.split()
+        if len(parts) >= 2 and parts[0] == f"{kernel}_traffic_bytes_per_launch:":
+            try:
+                return int(float(parts[1]))
+            except ValueError:
+                return None
+    return None
+
+
+def cpu_baseline(w, b, ws):
+    """The fp64 oracle, as it stands, on this machine's host cores: one full layer call."""
+    import numpy as np
+
+    from oracle import lora_oracle as O
+
+    def layer_call():
+        O.segments(b.adapter_id, b.expert_id, w.n_adapters, w.n_experts)
+        e_arr = b.expert_id if b.expert_id is not None else np.zeros_like(b.adapter_id)
+        act = b.adapter_id >= 0
+        units = sorted(set(zip(b.adapter_id[act].tolist(), e_arr[act].tolist())))
+        for j, p in enumerate(w.projs):
+            A_units = [None] * w.n_keys
+            B_units = [None] * w.n_keys
+            for a, e in units:
+                A, B = ws.unit_arrays(a, 0, e, j)
+                A_units[a * w.n_experts + e] = A
+                B_units[a * w.n_experts + e] = B
+            O.delta(b.inputs[p.input], b.adapter_id, A_units, B_units, b.scale,
+                    n_adapters=w.n_adapters, n_experts=w.n_experts, expert_id=b.expert_id,
+                    src_row=None if p.input == "mid" else b.token_of_pair, y_in=b.y_in[p.name],
+                    want_v=False)
+
+    layer_call()                      # first call also builds/loads the oracle
+    times = []
+    t_all = time.perf_counter()
+    while len(times) < 3 or (time.perf_counter() - t_all < 10.0 and len(times) < 20):
+        t0 = time.perf_counter()
+        layer_call()
+        times.append(time.perf_counter() - t0)
+    t = float(np.median(times))
+    return dict(value=w.tokens / t, unit="tokens/s", cores=O.n_threads(), kind="oracle",
+                sample=f"full layer call of {w.name} ({w.tokens} tokens, {w.pairs} rows, "
+                       f"{len(w.projs)} projections), median of {len(times)} runs, {t:.3f} s each")
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU; this build has no multi-GPU path (--gpus must be 1)",
+              file=sys.stderr)
+        return 2
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        return 1
+    torch.cuda.set_device(0)
+    main_res = measure(args.workload, args, args.steps, args.warmup, not args.no_cpu_baseline)
+    out = {
+        "metric": "LoRA-delta tokens/s (MoE-LoRA decode layer call) on 1 MI355X",
+        "value": round(main_res["tokens_per_s"], 1),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(main_res["ms_per_step"], 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": args.workload, "layers_in_pool": main_res["layers_in_pool"],
+                   "weights": "hot (one layer)" if args.hot else "cold (layer rotation)",
+                   "seed": args.seed, "segments": main_res["segments"], "rows": main_res["pairs"]},
+        "hbm_gbs": round(main_res["step_gbs"], 1),
+        "hbm_frac_of_peak": round(main_res["step_frac_of_peak"], 4),
+        "algorithmic_bytes_per_step": main_res["algorithmic_bytes"],
+        "pairs_per_s": round(main_res["pairs_per_s"], 1),
+        "phases": {k: {"us": round(v["us"], 2), "GB/s": round(v["gbs"], 1)}
+                   for k, v in main_res["phases"].items()},
+        "roofline": main_res["roofline"],
+    }
+    if "cpu_baseline" in main_res:
+        out["cpu_baseline"] = main_res["cpu_baseline"]
+    if args.all:
+        extra = {}
+        for name in ("dense_small", "llama8b_decode", "prefill", "finegrained_moe_decode"):
+            if name == args.workload:
+                continue
+            r = measure(name, args, max(20, args.steps // 4), max(5, args.warmup // 2), False)
+            extra[name] = {"ms_per_step": round(r["ms_per_step"], 5),
+                           "tokens_per_s": round(r["tokens_per_s"], 1),
+                           "hbm_gbs": round(r["step_gbs"], 1),
+                           "hbm_frac_of_peak": round(r["step_frac_of_peak"], 4),
+                           "algorithmic_bytes_per_step": r["algorithmic_bytes"],
+                           "phases": {k: {"us": round(v["us"], 2), "GB/s": round(v["gbs"], 1)}
+                                      for k, v in r["phases"].items()}}
+        out["extra"] = extra
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

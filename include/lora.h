@@ -1,0 +1,240 @@
+/*
+ * liblora — batched heterogeneous-adapter LoRA delta for one MI355X (gfx950).
+ *
+ * Every row of a batch carries its own adapter id and, in MoE layers, its routed expert
+ * id, and receives  y[row] += scale[adapter] * (x[row] * A) * B  with the A and B of its
+ * (adapter, layer, expert) unit.
+ *
+ * Conventions that hold for every call:
+ *   - returns LORA_OK (0) or a negative lora_status; never throws, never exits;
+ *   - "device" pointers are HIP device memory owned by the caller; "host" pointers are
+ *     ordinary process memory; the library allocates no device memory at all: the pool
+ *     lives in a caller-provided slab, intermediates in caller-provided workspaces;
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream); all device
+ *     work is enqueued on it and nothing synchronises, so outputs are ready when the
+ *     stream reaches that point;
+ *   - activations and outputs are row-major; bf16 is passed as 16-bit patterns;
+ *   - device pointers to activations, outputs and workspaces must be 16-byte aligned and
+ *     leading dimensions (in elements) multiples of 8;
+ *   - host-detectable mistakes (NULL, negative sizes, bad rank, misalignment, short
+ *     buffers, out-of-range layer/projection) are reported before any device work is
+ *     enqueued; data-dependent ones (an id outside the pool) cannot be, so they raise a
+ *     bit in the device status word of lora_segments and the row is treated as id -1.
+ */
+#ifndef LORA_H
+#define LORA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum lora_status {
+    LORA_OK = 0,
+    LORA_ERR_INVALID_ARG = -1,      /* NULL where a pointer is required, negative count, bad enum */
+    LORA_ERR_BAD_SHAPE = -2,        /* widths not multiples of 8, ld < width, layer/proj out of range */
+    LORA_ERR_UNSUPPORTED_RANK = -3, /* rank not in {8, 16, 32, 64} */
+    LORA_ERR_BUFFER_TOO_SMALL = -4, /* slab or workspace smaller than the size query says */
+    LORA_ERR_NOT_REGISTERED = -5,   /* pool handle NULL or destroyed, segments not built */
+    LORA_ERR_HIP = -6,              /* a HIP runtime call failed; see lora_last_hip_error */
+    LORA_ERR_MISALIGNED = -7,       /* pointer not 16-byte (slab: 256-byte) aligned */
+    LORA_ERR_TOO_LARGE = -8         /* P or key space beyond what the segment builder handles */
+} lora_status;
+
+enum { LORA_DTYPE_BF16 = 0, LORA_DTYPE_F32 = 1 };
+enum { LORA_MOE_UPGATE = 0, LORA_MOE_DOWN = 1 };
+enum { LORA_MAX_PROJ = 8, LORA_MAX_ROWS = 1 << 14 };
+
+/* bits of the device status word written by lora_build_segments */
+enum { LORA_STATUS_BAD_ADAPTER = 1u, LORA_STATUS_BAD_EXPERT = 2u };
+
+const char *lora_strerror(int status);
+/* Text of the last HIP error seen by this thread's calls ("" if none). */
+const char *lora_last_hip_error(void);
+
+/* ------------------------------------------------------------------------------------
+ * Adapter pool and pointer table.
+ *
+ * Sec. 4.1 abstracts the adapters as an n x l x e tensor of units, one unit holding the
+ * LoRA matrices of one expert at one layer of one adapter; Sec. 4.2 keeps a working set
+ * of adapters resident in GPU memory.  Here a unit carries, for each of n_proj
+ * projections, A (h_in x rank) and B (rank x h_out) in bf16 (Sec. 2.2), and the pool is
+ * the resident set: one slab in HBM plus a device table with one entry per
+ * (layer, adapter, expert, projection) giving the addresses of that unit's A and B, its
+ * rank and its adapter's scale.
+ *
+ * The slab stores A and B re-tiled for the kernels (see lora_pool_unit_layout); callers
+ * hand over plain row-major matrices and the library repacks them on the device.
+ * An adapter whose own rank is below the pool rank is zero-padded, which is exact.
+ * MoE pools used with lora_moe_apply have n_proj = 3 in the order gate, up, down.
+ * ------------------------------------------------------------------------------------ */
+typedef struct lora_proj_desc {
+    int32_t h_in;   /* input width of the projection, multiple of 8 */
+    int32_t h_out;  /* output width, multiple of 8 */
+} lora_proj_desc;
+
+typedef struct lora_pool_desc {
+    int32_t n_adapters;            /* n >= 1 */
+    int32_t n_layers;              /* l >= 1 */
+    int32_t n_experts;             /* e >= 1 (1 = dense layer) */
+    int32_t n_proj;                /* 1 .. LORA_MAX_PROJ */
+    int32_t rank;                  /* pool rank: 8, 16, 32 or 64 */
+    int32_t dtype;                 /* LORA_DTYPE_BF16 */
+    lora_proj_desc proj[LORA_MAX_PROJ];
+    const float *scale;            /* host, [n_adapters]; NULL = 1.0 for all */
+    const int32_t *adapter_rank;   /* host, [n_adapters], each 1..rank; NULL = pool rank */
+} lora_pool_desc;
+
+typedef struct lora_pool lora_pool; /* opaque host handle */
+
+/* Bytes the slab must have for this description (table + all units), 0 if invalid. */
+size_t lora_pool_bytes(const lora_pool_desc *d);
+
+/*
+ * Lay the pool out inside `slab` (device, 256-byte aligned, >= lora_pool_bytes) and write
+ * the device table.  A_src / B_src: host arrays of n_adapters*n_layers*n_experts*n_proj
+ * device pointers in the order [adapter][layer][expert][proj], each to a row-major bf16
+ * A[h_in][adapter_rank] / B[adapter_rank][h_out]; both NULL = leave every unit zero (load
+ * later with lora_pool_load_*).  The slab must stay alive and untouched by the caller until
+ * lora_pool_destroy.  On success *out receives the handle.
+ */
+int lora_register_pool(const lora_pool_desc *d, void *slab, size_t slab_bytes,
+                       const void *const *A_src, const void *const *B_src,
+                       void *stream, lora_pool **out);
+
+/* Repack one unit's projection from row-major device matrices (bf16). */
+int lora_pool_load_unit(lora_pool *pool, int adapter, int layer, int expert, int proj,
+                        const void *A, const void *B, void *stream);
+
+/*
+ * Repack all experts and projections of one (adapter, layer) from one contiguous device
+ * buffer laid out [expert][proj]{ A[h_in][r], B[r][h_out] } with r = that adapter's rank
+ * (Sec. 5.3 loads adapters layer by layer; this is the unit of such a load).
+ */
+int lora_pool_load_adapter_layer(lora_pool *pool, int adapter, int layer, const void *src,
+                                 void *stream);
+
+/* Inverse of the repacking: write one unit's projection back as row-major bf16
+ * A[h_in][rank] and B[rank][h_out] (pool rank, zero padding included). */
+int lora_pool_read_unit(const lora_pool *pool, int adapter, int layer, int expert, int proj,
+                        void *A_out, void *B_out, void *stream);
+
+/* Host view of one table entry: byte offsets of the packed A and B inside the slab,
+ * their sizes, the unit's rank and scale. Any out pointer may be NULL. */
+int lora_pool_unit_layout(const lora_pool *pool, int adapter, int layer, int expert, int proj,
+                          size_t *A_offset, size_t *A_bytes, size_t *B_offset, size_t *B_bytes,
+                          int32_t *rank, float *scale);
+
+/* Device address of the table (entries of 32 bytes: A*, B*, float scale, int32 rank, pad),
+ * ordered [layer][adapter][expert][proj]. */
+const void *lora_pool_device_table(const lora_pool *pool);
+
+int lora_pool_destroy(lora_pool *pool);
+
+/* ------------------------------------------------------------------------------------
+ * Segments.
+ *
+ * App. A.2.2: rows that share an adapter are aggregated into one GEMM so that the
+ * adapter's weights are read once; with expert-specific matrices (Sec. 2.3) the rows that
+ * share (adapter, expert).  lora_build_segments produces the one canonical grouping:
+ *   key = adapter * n_experts + expert;
+ *   rows with adapter -1 (no LoRA) or an out-of-range id are left out;
+ *   perm[0 .. P_act) lists the remaining row indices by ascending key, original order
+ *   kept inside a key (a stable counting sort);
+ *   seg_key[s], s < S: key of the s-th non-empty group; seg_start[s] its first position
+ *   in perm; seg_start[S] = P_act;
+ *   counts = { S, P_act, n_tiles, 0 }.
+ * Results are deterministic and bit-identical run to run.  Entries of perm, seg_start,
+ * seg_key beyond the stated ranges are unspecified.  tiles (row blocks of at most
+ * tile_rows rows that never cross a segment) are what the compute kernels iterate over.
+ * ------------------------------------------------------------------------------------ */
+typedef struct lora_tile {   /* device record, 16 bytes */
+    int32_t key;             /* segment key of the tile */
+    int32_t row0;            /* first position in perm */
+    int32_t n_rows;          /* 1 .. tile_rows */
+    int32_t seg;             /* index of the segment */
+} lora_tile;
+
+typedef struct lora_segments {
+    int32_t P;               /* host: rows the ids describe; set by lora_build_segments */
+    int32_t tile_rows;       /* host: set by lora_build_segments */
+    int32_t *perm;           /* device [P] */
+    int32_t *seg_start;      /* device [P + 1] */
+    int32_t *seg_key;        /* device [P] */
+    lora_tile *tiles;        /* device [P] */
+    int32_t *counts;         /* device [4] */
+    uint32_t *status;        /* device [1]: 0 or LORA_STATUS_* bits of this call */
+} lora_segments;
+
+size_t lora_segments_ws_bytes(int P);
+
+/*
+ * adapter_id: device int32 [P], -1 = no adapter.  expert_id: device int32 [P] or NULL for a
+ * dense layer.  P = 0 is a valid no-op that writes counts = 0.  P <= LORA_MAX_ROWS.
+ * `seg`: the caller fills the six device pointers; the call fills P and tile_rows.
+ * ws: device scratch of lora_segments_ws_bytes(P) (a small reserve: the builder sorts in LDS).
+ */
+int lora_build_segments(const lora_pool *pool, const int32_t *adapter_id,
+                        const int32_t *expert_id, int P, lora_segments *seg,
+                        void *ws, size_t ws_bytes, void *stream);
+
+/* ------------------------------------------------------------------------------------
+ * Shrink and expand (App. A.2.2 names the two phases; Sec. 2.2 defines the product).
+ *
+ * lora_shrink:  v = gather(x) * A.   Row i of the sorted order reads x row
+ *   src_row[perm[i]] (src_row NULL: perm[i]) — Sec. 5.2: activations are scattered and
+ *   must be gathered.  x: device bf16, row stride ldx elements.
+ *   v: device fp32 workspace of lora_v_bytes(pool, proj, P) bytes; it holds per-K-slice
+ *   partial sums in sorted-row order and is meant only to be passed to lora_expand with
+ *   the same pool, layer, proj and segments.
+ * lora_expand:  y[perm[i]] += scale * v_i * B   (Sec. 2.2: the update is added to the base
+ *   output; Fig. 7b: final addition of the two outputs).  y: device, row stride ldy
+ *   elements, bf16 (read, add in fp32, round to nearest even, write) or fp32.  Rows that
+ *   are not in perm are never read or written.  x and y must not overlap.
+ * ------------------------------------------------------------------------------------ */
+size_t lora_v_bytes(const lora_pool *pool, int proj, int P);
+
+int lora_shrink(const lora_pool *pool, int layer, int proj, const void *x, int64_t ldx,
+                const int32_t *src_row, const lora_segments *seg, float *v, void *stream);
+
+int lora_expand(const lora_pool *pool, int layer, int proj, const float *v,
+                const lora_segments *seg, void *y, int64_t ldy, int out_dtype, void *stream);
+
+/* ------------------------------------------------------------------------------------
+ * MoE application (Sec. 3: the LoRA computation runs twice per MoE layer, for the
+ * up/gate and for the down projection; Sec. 4.1: a batch of b requests with top-k routing
+ * activates b*k units per layer).  Rows are (token, expert) pairs.
+ *
+ * LORA_MOE_UPGATE: in = token activations x[T][ld_in] (bf16); pair p reads row
+ *   token_of_pair[p]; y0[P][ldy] += delta of projection 0 (gate), y1[P][ldy] += delta of
+ *   projection 1 (up).  Both projections share one pass over x.
+ * LORA_MOE_DOWN: in = per-pair activations hmid[P][ld_in]; token_of_pair ignored;
+ *   y0[P][ldy] += delta of projection 2 (down); y1 ignored.
+ * Outputs are bf16, one row per pair (routing weights are applied by the caller after).
+ * ws: device scratch of lora_moe_ws_bytes(pool, P).
+ * ------------------------------------------------------------------------------------ */
+size_t lora_moe_ws_bytes(const lora_pool *pool, int P);
+
+int lora_moe_apply(const lora_pool *pool, int layer, int which, const void *in, int64_t ld_in,
+                   const int32_t *token_of_pair, const lora_segments *seg,
+                   void *y0, void *y1, int64_t ldy, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * The two phases of lora_moe_apply as separate calls (App. A.2.2 reports shrink and expand
+ * separately): lora_moe_shrink leaves the intermediate in ws, lora_moe_expand consumes it.
+ * lora_moe_apply(...) is exactly lora_moe_shrink(...) followed by lora_moe_expand(...) with
+ * the same pool, layer, which, segments and ws.
+ */
+int lora_moe_shrink(const lora_pool *pool, int layer, int which, const void *in, int64_t ld_in,
+                    const int32_t *token_of_pair, const lora_segments *seg,
+                    void *ws, size_t ws_bytes, void *stream);
+
+int lora_moe_expand(const lora_pool *pool, int layer, int which, const lora_segments *seg,
+                    void *y0, void *y1, int64_t ldy, void *ws, size_t ws_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LORA_H */

@@ -1,0 +1,710 @@
+// C-ABI entry points: argument checks, pool bookkeeping, launch geometry.
+// Every check that can be made on the host happens before the first HIP call, so a bad
+// call costs nothing on the device and can be exercised on a machine without a GPU.
+#include <stdlib.h>
+#include <string.h>
+
+#include <algorithm>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "lora_internal.h"
+
+using namespace lora;
+
+namespace {
+
+constexpr uint32_t kPoolMagic = 0x4C6F5241u;  // "LoRA"
+
+thread_local std::string g_hip_error;
+
+int hip_fail(hipError_t e)
+{
+    g_hip_error = hipGetErrorString(e);
+    return LORA_ERR_HIP;
+}
+
+#define LORA_HIP(expr)                                  \
+    do {                                                \
+        hipError_t e_ = (expr);                         \
+        if (e_ != hipSuccess) return hip_fail(e_);      \
+    } while (0)
+
+bool rank_ok(int r) { return r == 8 || r == 16 || r == 32 || r == 64; }
+bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+int env_int(const char *name, int dflt, int lo, int hi)
+{
+    const char *v = getenv(name);
+    if (!v || !*v) return dflt;
+    long x = strtol(v, nullptr, 10);
+    if (x < lo || x > hi) return dflt;
+    return (int)x;
+}
+
+int cu_count()
+{
+    static int n = 0;
+    if (n == 0) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+            n = v;
+        else
+            n = 256;
+    }
+    return n;
+}
+
+}  // namespace
+
+struct lora_pool {
+    uint32_t magic;
+    lora_pool_desc d;
+    std::vector<float> scale;
+    std::vector<int32_t> arank;
+    char *slab;
+    size_t slab_bytes;
+    size_t table_bytes;
+    size_t unit_bytes;                    // all projections of one (layer, adapter, expert)
+    size_t A_off[LORA_MAX_PROJ], A_bytes[LORA_MAX_PROJ];
+    size_t B_off[LORA_MAX_PROJ], B_bytes[LORA_MAX_PROJ];
+    std::vector<Unit> table;              // host mirror of the device table
+
+    size_t unit_base(int layer, int adapter, int expert) const
+    {
+        return table_bytes +
+               (((size_t)layer * d.n_adapters + adapter) * d.n_experts + expert) * unit_bytes;
+    }
+    size_t table_index(int layer, int adapter, int expert, int proj) const
+    {
+        return (((size_t)layer * d.n_adapters + adapter) * d.n_experts + expert) * d.n_proj + proj;
+    }
+    const Unit *device_table() const { return reinterpret_cast<const Unit *>(slab); }
+};
+
+namespace {
+
+int check_desc(const lora_pool_desc *d)
+{
+    if (!d) return LORA_ERR_INVALID_ARG;
+    if (d->n_adapters < 1 || d->n_layers < 1 || d->n_experts < 1) return LORA_ERR_INVALID_ARG;
+    if (d->n_proj < 1 || d->n_proj > LORA_MAX_PROJ) return LORA_ERR_INVALID_ARG;
+    if (d->dtype != LORA_DTYPE_BF16) return LORA_ERR_INVALID_ARG;
+    if (!rank_ok(d->rank)) return LORA_ERR_UNSUPPORTED_RANK;
+    if ((int64_t)d->n_adapters * d->n_experts >= (int64_t)1 << 30) return LORA_ERR_TOO_LARGE;
+    for (int i = 0; i < d->n_proj; ++i) {
+        const lora_proj_desc &p = d->proj[i];
+        if (p.h_in < 8 || p.h_out < 8 || (p.h_in % 8) || (p.h_out % 8)) return LORA_ERR_BAD_SHAPE;
+    }
+    if (d->adapter_rank)
+        for (int a = 0; a < d->n_adapters; ++a)
+            if (d->adapter_rank[a] < 1 || d->adapter_rank[a] > d->rank) return LORA_ERR_UNSUPPORTED_RANK;
+    return LORA_OK;
+}
+
+struct Layout {
+    size_t table_bytes, unit_bytes, total;
+    size_t A_off[LORA_MAX_PROJ], A_bytes[LORA_MAX_PROJ], B_off[LORA_MAX_PROJ], B_bytes[LORA_MAX_PROJ];
+};
+
+Layout layout_of(const lora_pool_desc &d)
+{
+    Layout L;
+    const size_t n_units = (size_t)d.n_layers * d.n_adapters * d.n_experts;
+    L.table_bytes = align_up(n_units * d.n_proj * sizeof(Unit), 256);
+    size_t off = 0;
+    for (int i = 0; i < d.n_proj; ++i) {
+        L.A_off[i] = off;
+        L.A_bytes[i] = packed_A_bytes(d.proj[i].h_in, d.rank);
+        off = align_up(off + L.A_bytes[i], 256);
+        L.B_off[i] = off;
+        L.B_bytes[i] = packed_B_bytes(d.proj[i].h_out, d.rank);
+        off = align_up(off + L.B_bytes[i], 256);
+    }
+    L.unit_bytes = off;
+    L.total = L.table_bytes + n_units * L.unit_bytes;
+    return L;
+}
+
+int check_pool(const lora_pool *p)
+{
+    if (!p || p->magic != kPoolMagic) return LORA_ERR_NOT_REGISTERED;
+    return LORA_OK;
+}
+
+int check_unit(const lora_pool *p, int adapter, int layer, int expert, int proj)
+{
+    if (adapter < 0 || adapter >= p->d.n_adapters || layer < 0 || layer >= p->d.n_layers ||
+        expert < 0 || expert >= p->d.n_experts || proj < 0 || proj >= p->d.n_proj)
+        return LORA_ERR_BAD_SHAPE;
+    return LORA_OK;
+}
+
+// upper bound on the number of row tiles a batch of P rows can produce
+int64_t tiles_upper_bound(const lora_pool *p, int P)
+{
+    const int64_t keys = (int64_t)p->d.n_adapters * p->d.n_experts;
+    return std::min<int64_t>(P, std::min<int64_t>(keys, P) + P / kTileRows);
+}
+
+struct KSplit {
+    int n_parts, kb_per_part;
+};
+
+// How the K range of a shrink is cut into parts: enough work items to fill the chip when the
+// batch has few tiles, and no part longer than kPartKBlocks K-blocks.  Depends only on the
+// pool and P, so lora_shrink, lora_expand and lora_v_bytes agree.
+KSplit ksplit_of(const lora_pool *p, int proj, int P)
+{
+    const int kblocks = kblocks_of(p->d.proj[proj].h_in);
+    const int64_t tub = std::max<int64_t>(1, tiles_upper_bound(p, P));
+    static const int target = env_int("LORA_SHRINK_ITEMS", 1024, 1, 1 << 20);
+    int want = (int)std::min<int64_t>((target + tub - 1) / tub, kMaxParts);
+    int by_size = (kblocks + kPartKBlocks - 1) / kPartKBlocks;
+    int n = std::max(want, by_size);
+    n = std::min(n, std::max(1, kblocks / 4));
+    n = std::min(n, kMaxParts);
+    int per = (kblocks + n - 1) / n;
+    per = (per + 3) / 4 * 4;
+    KSplit k;
+    k.kb_per_part = per;
+    k.n_parts = (kblocks + per - 1) / per;
+    return k;
+}
+
+int check_segments(const lora_segments *s)
+{
+    if (!s) return LORA_ERR_INVALID_ARG;
+    if (s->P < 0 || s->tile_rows != kTileRows) return LORA_ERR_NOT_REGISTERED;
+    if (s->P > 0 && (!s->perm || !s->seg_start || !s->seg_key || !s->tiles || !s->counts || !s->status))
+        return LORA_ERR_INVALID_ARG;
+    return LORA_OK;
+}
+
+int do_shrink(const lora_pool *pool, int layer, int proj0, int n_fused, const void *x, int64_t ldx,
+              const int32_t *src_row, const lora_segments *seg, float *v0, float *v1, hipStream_t st)
+{
+    const lora_proj_desc &pd = pool->d.proj[proj0];
+    const KSplit ks = ksplit_of(pool, proj0, seg->P);
+    ShrinkParams sp;
+    memset(&sp, 0, sizeof sp);
+    sp.units = pool->device_table() + pool->table_index(layer, 0, 0, 0);
+    sp.n_proj = pool->d.n_proj;
+    sp.proj0 = proj0;
+    sp.n_fused = n_fused;
+    sp.x = static_cast<const uint16_t *>(x);
+    sp.ldx = ldx;
+    sp.src_row = src_row;
+    sp.perm = seg->perm;
+    sp.tiles = seg->tiles;
+    sp.counts = seg->counts;
+    sp.v[0] = v0;
+    sp.v[1] = v1;
+    sp.P = seg->P;
+    sp.h_in = pd.h_in;
+    sp.n_parts = ks.n_parts;
+    sp.kb_per_part = ks.kb_per_part;
+    sp.rank = pool->d.rank;
+    static const int per_cu = env_int("LORA_SHRINK_WGS_PER_CU", 4, 1, 64);
+    const int64_t items = tiles_upper_bound(pool, seg->P) * ks.n_parts;
+    sp.grid = (int)std::min<int64_t>(items, (int64_t)cu_count() * per_cu);
+    LORA_HIP(launch_shrink(sp, st));
+    return LORA_OK;
+}
+
+int do_expand(const lora_pool *pool, int layer, int proj0, int n_fused, const float *v0,
+              const float *v1, const lora_segments *seg, void *y0, void *y1, int64_t ldy,
+              int out_dtype, hipStream_t st)
+{
+    const lora_proj_desc &pd = pool->d.proj[proj0];
+    const KSplit ks = ksplit_of(pool, proj0, seg->P);
+    ExpandParams ep;
+    memset(&ep, 0, sizeof ep);
+    ep.units = pool->device_table() + pool->table_index(layer, 0, 0, 0);
+    ep.n_proj = pool->d.n_proj;
+    ep.proj0 = proj0;
+    ep.n_fused = n_fused;
+    ep.v[0] = v0;
+    ep.v[1] = v1;
+    ep.n_parts = ks.n_parts;
+    ep.P = seg->P;
+    ep.perm = seg->perm;
+    ep.tiles = seg->tiles;
+    ep.counts = seg->counts;
+    ep.y[0] = y0;
+    ep.y[1] = y1;
+    ep.ldy = ldy;
+    ep.h_out = pd.h_out;
+    ep.n_chunks = chunks_of(pd.h_out);
+    // waves per workgroup: the largest of 4, 3, 2 that divides the chunk count, else 4
+    ep.waves = 4;
+    if (ep.n_chunks % 4 != 0) {
+        if (ep.n_chunks % 3 == 0) ep.waves = 3;
+        else if (ep.n_chunks % 2 == 0) ep.waves = 2;
+        else if (ep.n_chunks < 4) ep.waves = ep.n_chunks;
+    }
+    const int groups = (ep.n_chunks + ep.waves - 1) / ep.waves;
+    const int64_t tub = std::max<int64_t>(1, tiles_upper_bound(pool, seg->P));
+    static const int target = env_int("LORA_EXPAND_ITEMS", 2048, 1, 1 << 20);
+    int64_t slices = (target + tub * n_fused - 1) / (tub * n_fused);
+    ep.n_slices = (int)std::max<int64_t>(1, std::min<int64_t>(slices, groups));
+    ep.out_f32 = out_dtype == LORA_DTYPE_F32;
+    ep.rank = pool->d.rank;
+    static const int per_cu = env_int("LORA_EXPAND_WGS_PER_CU", 4, 1, 64);
+    const int64_t items = tub * n_fused * ep.n_slices;
+    ep.grid = (int)std::min<int64_t>(items, (int64_t)cu_count() * per_cu);
+    LORA_HIP(launch_expand(ep, st));
+    return LORA_OK;
+}
+
+int check_act(const void *ptr, int64_t ld, int width, size_t elem)
+{
+    if (!ptr) return LORA_ERR_INVALID_ARG;
+    if (!aligned(ptr, 16)) return LORA_ERR_MISALIGNED;
+    if (ld < width || (ld % 8) != 0) return LORA_ERR_BAD_SHAPE;
+    (void)elem;
+    return LORA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *lora_strerror(int status)
+{
+    switch (status) {
+    case LORA_OK: return "ok";
+    case LORA_ERR_INVALID_ARG: return "invalid argument";
+    case LORA_ERR_BAD_SHAPE: return "bad shape, leading dimension or index";
+    case LORA_ERR_UNSUPPORTED_RANK: return "unsupported LoRA rank (supported: 8, 16, 32, 64)";
+    case LORA_ERR_BUFFER_TOO_SMALL: return "buffer smaller than its size query";
+    case LORA_ERR_NOT_REGISTERED: return "pool not registered or segments not built";
+    case LORA_ERR_HIP: return "HIP runtime error";
+    case LORA_ERR_MISALIGNED: return "misaligned pointer";
+    case LORA_ERR_TOO_LARGE: return "batch or key space too large";
+    default: return "unknown status";
+    }
+}
+
+const char *lora_last_hip_error(void) { return g_hip_error.c_str(); }
+
+size_t lora_pool_bytes(const lora_pool_desc *d)
+{
+    if (check_desc(d) != LORA_OK) return 0;
+    return layout_of(*d).total;
+}
+
+int lora_register_pool(const lora_pool_desc *d, void *slab, size_t slab_bytes,
+                       const void *const *A_src, const void *const *B_src, void *stream,
+                       lora_pool **out)
+{
+    if (!out) return LORA_ERR_INVALID_ARG;
+    *out = nullptr;
+    int rc = check_desc(d);
+    if (rc != LORA_OK) return rc;
+    if (!slab) return LORA_ERR_INVALID_ARG;
+    if ((A_src == nullptr) != (B_src == nullptr)) return LORA_ERR_INVALID_ARG;
+    if (!aligned(slab, 256)) return LORA_ERR_MISALIGNED;
+    const Layout L = layout_of(*d);
+    if (slab_bytes < L.total) return LORA_ERR_BUFFER_TOO_SMALL;
+    const size_t n_src = (size_t)d->n_adapters * d->n_layers * d->n_experts * d->n_proj;
+    if (A_src)
+        for (size_t i = 0; i < n_src; ++i) {
+            if (!A_src[i] || !B_src[i]) return LORA_ERR_INVALID_ARG;
+            if (!aligned(A_src[i], 2) || !aligned(B_src[i], 2)) return LORA_ERR_MISALIGNED;
+        }
+
+    lora_pool *p = new (std::nothrow) lora_pool();
+    if (!p) return LORA_ERR_INVALID_ARG;
+    p->magic = kPoolMagic;
+    p->d = *d;
+    p->scale.assign(d->n_adapters, 1.0f);
+    if (d->scale) p->scale.assign(d->scale, d->scale + d->n_adapters);
+    p->arank.assign(d->n_adapters, d->rank);
+    if (d->adapter_rank) p->arank.assign(d->adapter_rank, d->adapter_rank + d->n_adapters);
+    p->d.scale = nullptr;
+    p->d.adapter_rank = nullptr;
+    p->slab = static_cast<char *>(slab);
+    p->slab_bytes = slab_bytes;
+    p->table_bytes = L.table_bytes;
+    p->unit_bytes = L.unit_bytes;
+    for (int i = 0; i < d->n_proj; ++i) {
+        p->A_off[i] = L.A_off[i];
+        p->A_bytes[i] = L.A_bytes[i];
+        p->B_off[i] = L.B_off[i];
+        p->B_bytes[i] = L.B_bytes[i];
+    }
+    p->table.resize((size_t)d->n_layers * d->n_adapters * d->n_experts * d->n_proj);
+    for (int l = 0; l < d->n_layers; ++l)
+        for (int a = 0; a < d->n_adapters; ++a)
+            for (int e = 0; e < d->n_experts; ++e)
+                for (int j = 0; j < d->n_proj; ++j) {
+                    Unit &u = p->table[p->table_index(l, a, e, j)];
+                    const size_t base = p->unit_base(l, a, e);
+                    u.A = reinterpret_cast<const uint16_t *>(p->slab + base + L.A_off[j]);
+                    u.B = reinterpret_cast<const uint16_t *>(p->slab + base + L.B_off[j]);
+                    u.scale = p->scale[a];
+                    u.rank = p->arank[a];
+                    u.pad[0] = u.pad[1] = 0;
+                }
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipError_t e = hipMemcpyAsync(p->slab, p->table.data(), p->table.size() * sizeof(Unit),
+                                  hipMemcpyHostToDevice, st);
+    if (e == hipSuccess && !A_src)
+        e = hipMemsetAsync(p->slab + L.table_bytes, 0, L.total - L.table_bytes, st);
+    if (e != hipSuccess) {
+        p->magic = 0;
+        delete p;
+        return hip_fail(e);
+    }
+    if (A_src) {
+        size_t i = 0;
+        for (int a = 0; a < d->n_adapters; ++a)
+            for (int l = 0; l < d->n_layers; ++l)
+                for (int ex = 0; ex < d->n_experts; ++ex)
+                    for (int j = 0; j < d->n_proj; ++j, ++i) {
+                        rc = lora_pool_load_unit(p, a, l, ex, j, A_src[i], B_src[i], stream);
+                        if (rc != LORA_OK) {
+                            p->magic = 0;
+                            delete p;
+                            return rc;
+                        }
+                    }
+    }
+    *out = p;
+    return LORA_OK;
+}
+
+int lora_pool_load_unit(lora_pool *pool, int adapter, int layer, int expert, int proj,
+                        const void *A, const void *B, void *stream)
+{
+    int rc = check_pool(pool);
+    if (rc != LORA_OK) return rc;
+    rc = check_unit(pool, adapter, layer, expert, proj);
+    if (rc != LORA_OK) return rc;
+    if (!A || !B) return LORA_ERR_INVALID_ARG;
+    if (!aligned(A, 2) || !aligned(B, 2)) return LORA_ERR_MISALIGNED;
+    const size_t base = pool->unit_base(layer, adapter, expert);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    PackParams pp;
+    pp.src = static_cast<const uint16_t *>(A);
+    pp.src_stride = 0;
+    pp.dst = reinterpret_cast<uint16_t *>(pool->slab + base + pool->A_off[proj]);
+    pp.dst_stride = 0;
+    pp.n_units = 1;
+    pp.h = pool->d.proj[proj].h_in;
+    pp.rank = pool->d.rank;
+    pp.src_rank = pool->arank[adapter];
+    LORA_HIP(launch_pack_A(pp, st));
+    pp.src = static_cast<const uint16_t *>(B);
+    pp.dst = reinterpret_cast<uint16_t *>(pool->slab + base + pool->B_off[proj]);
+    pp.h = pool->d.proj[proj].h_out;
+    LORA_HIP(launch_pack_B(pp, st));
+    return LORA_OK;
+}
+
+int lora_pool_load_adapter_layer(lora_pool *pool, int adapter, int layer, const void *src,
+                                 void *stream)
+{
+    int rc = check_pool(pool);
+    if (rc != LORA_OK) return rc;
+    rc = check_unit(pool, adapter, layer, 0, 0);
+    if (rc != LORA_OK) return rc;
+    if (!src) return LORA_ERR_INVALID_ARG;
+    if (!aligned(src, 2)) return LORA_ERR_MISALIGNED;
+    const int r = pool->arank[adapter];
+    int64_t unit_elems = 0;
+    for (int j = 0; j < pool->d.n_proj; ++j)
+        unit_elems += ((int64_t)pool->d.proj[j].h_in + pool->d.proj[j].h_out) * r;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const size_t base = pool->unit_base(layer, adapter, 0);
+    int64_t off = 0;
+    for (int j = 0; j < pool->d.n_proj; ++j) {
+        PackParams pp;
+        pp.src = static_cast<const uint16_t *>(src) + off;
+        pp.src_stride = unit_elems;
+        pp.dst = reinterpret_cast<uint16_t *>(pool->slab + base + pool->A_off[j]);
+        pp.dst_stride = (int64_t)(pool->unit_bytes / 2);
+        pp.n_units = pool->d.n_experts;
+        pp.h = pool->d.proj[j].h_in;
+        pp.rank = pool->d.rank;
+        pp.src_rank = r;
+        LORA_HIP(launch_pack_A(pp, st));
+        off += (int64_t)pool->d.proj[j].h_in * r;
+        pp.src = static_cast<const uint16_t *>(src) + off;
+        pp.dst = reinterpret_cast<uint16_t *>(pool->slab + base + pool->B_off[j]);
+        pp.h = pool->d.proj[j].h_out;
+        LORA_HIP(launch_pack_B(pp, st));
+        off += (int64_t)pool->d.proj[j].h_out * r;
+    }
+    return LORA_OK;
+}
+
+int lora_pool_read_unit(const lora_pool *pool, int adapter, int layer, int expert, int proj,
+                        void *A_out, void *B_out, void *stream)
+{
+    int rc = check_pool(pool);
+    if (rc != LORA_OK) return rc;
+    rc = check_unit(pool, adapter, layer, expert, proj);
+    if (rc != LORA_OK) return rc;
+    if (!A_out || !B_out) return LORA_ERR_INVALID_ARG;
+    const size_t base = pool->unit_base(layer, adapter, expert);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    PackParams pp;
+    pp.src = reinterpret_cast<const uint16_t *>(pool->slab + base + pool->A_off[proj]);
+    pp.src_stride = 0;
+    pp.dst = static_cast<uint16_t *>(A_out);
+    pp.dst_stride = 0;
+    pp.n_units = 1;
+    pp.h = pool->d.proj[proj].h_in;
+    pp.rank = pool->d.rank;
+    pp.src_rank = pool->d.rank;
+    LORA_HIP(launch_unpack_A(pp, st));
+    pp.src = reinterpret_cast<const uint16_t *>(pool->slab + base + pool->B_off[proj]);
+    pp.dst = static_cast<uint16_t *>(B_out);
+    pp.h = pool->d.proj[proj].h_out;
+    LORA_HIP(launch_unpack_B(pp, st));
+    return LORA_OK;
+}
+
+int lora_pool_unit_layout(const lora_pool *pool, int adapter, int layer, int expert, int proj,
+                          size_t *A_offset, size_t *A_bytes, size_t *B_offset, size_t *B_bytes,
+                          int32_t *rank, float *scale)
+{
+    int rc = check_pool(pool);
+    if (rc != LORA_OK) return rc;
+    rc = check_unit(pool, adapter, layer, expert, proj);
+    if (rc != LORA_OK) return rc;
+    const size_t base = pool->unit_base(layer, adapter, expert);
+    if (A_offset) *A_offset = base + pool->A_off[proj];
+    if (A_bytes) *A_bytes = pool->A_bytes[proj];
+    if (B_offset) *B_offset = base + pool->B_off[proj];
+    if (B_bytes) *B_bytes = pool->B_bytes[proj];
+    if (rank) *rank = pool->arank[adapter];
+    if (scale) *scale = pool->scale[adapter];
+    return LORA_OK;
+}
+
+const void *lora_pool_device_table(const lora_pool *pool)
+{
+    if (check_pool(pool) != LORA_OK) return nullptr;
+    return pool->slab;
+}
+
+int lora_pool_destroy(lora_pool *pool)
+{
+    int rc = check_pool(pool);
+    if (rc != LORA_OK) return rc;
+    pool->magic = 0;
+    delete pool;
+    return LORA_OK;
+}
+
+size_t lora_segments_ws_bytes(int P)
+{
+    if (P < 0) return 0;
+    return 256;   // the builder sorts out of LDS; the global scratch is a reserve
+}
+
+int lora_build_segments(const lora_pool *pool, const int32_t *adapter_id, const int32_t *expert_id,
+                        int P, lora_segments *seg, void *ws, size_t ws_bytes, void *stream)
+{
+    int rc = check_pool(pool);
+    if (rc != LORA_OK) return rc;
+    if (!seg || P < 0) return LORA_ERR_INVALID_ARG;
+    if (P > LORA_MAX_ROWS) return LORA_ERR_TOO_LARGE;
+    if (!seg->counts || !seg->status) return LORA_ERR_INVALID_ARG;
+    if (P > 0) {
+        if (!adapter_id || !seg->perm || !seg->seg_start || !seg->seg_key || !seg->tiles || !ws)
+            return LORA_ERR_INVALID_ARG;
+        if (pool->d.n_experts > 1 && !expert_id) return LORA_ERR_INVALID_ARG;
+        if (!aligned(ws, 16) || !aligned(seg->tiles, 16)) return LORA_ERR_MISALIGNED;
+        if (ws_bytes < lora_segments_ws_bytes(P)) return LORA_ERR_BUFFER_TOO_SMALL;
+    }
+    seg->P = P;
+    seg->tile_rows = kTileRows;
+    SegParams sp;
+    memset(&sp, 0, sizeof sp);
+    sp.adapter_id = adapter_id;
+    sp.expert_id = expert_id;
+    sp.P = P;
+    sp.n_adapters = pool->d.n_adapters;
+    sp.n_experts = pool->d.n_experts;
+    sp.tile_rows = kTileRows;
+    const uint32_t n_keys = (uint32_t)pool->d.n_adapters * (uint32_t)pool->d.n_experts;
+    int bits = 0;
+    while ((n_keys >> bits) != 0) ++bits;      // the sentinel key n_keys must be representable
+    sp.passes = std::max(1, (bits + 7) / 8);
+    sp.perm = seg->perm;
+    sp.seg_start = seg->seg_start;
+    sp.seg_key = seg->seg_key;
+    sp.tiles = seg->tiles;
+    sp.counts = seg->counts;
+    sp.status = seg->status;
+    LORA_HIP(launch_segments(sp, static_cast<hipStream_t>(stream)));
+    return LORA_OK;
+}
+
+size_t lora_v_bytes(const lora_pool *pool, int proj, int P)
+{
+    if (check_pool(pool) != LORA_OK || proj < 0 || proj >= pool->d.n_proj || P < 0) return 0;
+    const KSplit ks = ksplit_of(pool, proj, P);
+    return align_up((size_t)ks.n_parts * std::max(P, 1) * pool->d.rank * sizeof(float), 256);
+}
+
+int lora_shrink(const lora_pool *pool, int layer, int proj, const void *x, int64_t ldx,
+                const int32_t *src_row, const lora_segments *seg, float *v, void *stream)
+{
+    int rc = check_pool(pool);
+    if (rc != LORA_OK) return rc;
+    rc = check_segments(seg);
+    if (rc != LORA_OK) return rc;
+    if (layer < 0 || layer >= pool->d.n_layers || proj < 0 || proj >= pool->d.n_proj)
+        return LORA_ERR_BAD_SHAPE;
+    if (seg->P == 0) return LORA_OK;
+    rc = check_act(x, ldx, pool->d.proj[proj].h_in, 2);
+    if (rc != LORA_OK) return rc;
+    if (!v) return LORA_ERR_INVALID_ARG;
+    if (!aligned(v, 16)) return LORA_ERR_MISALIGNED;
+    return do_shrink(pool, layer, proj, 1, x, ldx, src_row, seg, v, nullptr,
+                     static_cast<hipStream_t>(stream));
+}
+
+int lora_expand(const lora_pool *pool, int layer, int proj, const float *v,
+                const lora_segments *seg, void *y, int64_t ldy, int out_dtype, void *stream)
+{
+    int rc = check_pool(pool);
+    if (rc != LORA_OK) return rc;
+    rc = check_segments(seg);
+    if (rc != LORA_OK) return rc;
+    if (layer < 0 || layer >= pool->d.n_layers || proj < 0 || proj >= pool->d.n_proj)
+        return LORA_ERR_BAD_SHAPE;
+    if (out_dtype != LORA_DTYPE_BF16 && out_dtype != LORA_DTYPE_F32) return LORA_ERR_INVALID_ARG;
+    if (seg->P == 0) return LORA_OK;
+    rc = check_act(y, ldy, pool->d.proj[proj].h_out, out_dtype == LORA_DTYPE_F32 ? 4 : 2);
+    if (rc != LORA_OK) return rc;
+    if (!v) return LORA_ERR_INVALID_ARG;
+    if (!aligned(v, 16)) return LORA_ERR_MISALIGNED;
+    return do_expand(pool, layer, proj, 1, v, nullptr, seg, y, nullptr, ldy, out_dtype,
+                     static_cast<hipStream_t>(stream));
+}
+
+size_t lora_moe_ws_bytes(const lora_pool *pool, int P)
+{
+    if (check_pool(pool) != LORA_OK || pool->d.n_proj < 3 || P < 0) return 0;
+    return std::max(2 * lora_v_bytes(pool, 0, P), lora_v_bytes(pool, 2, P));
+}
+
+}  // extern "C"
+
+namespace {
+
+int moe_common_checks(const lora_pool *pool, int layer, int which, const lora_segments *seg,
+                      void *ws, size_t ws_bytes)
+{
+    int rc = check_pool(pool);
+    if (rc != LORA_OK) return rc;
+    rc = check_segments(seg);
+    if (rc != LORA_OK) return rc;
+    if (which != LORA_MOE_UPGATE && which != LORA_MOE_DOWN) return LORA_ERR_INVALID_ARG;
+    const lora_pool_desc &d = pool->d;
+    if (d.n_proj < 3 || layer < 0 || layer >= d.n_layers) return LORA_ERR_BAD_SHAPE;
+    if (d.proj[0].h_in != d.proj[1].h_in || d.proj[0].h_out != d.proj[1].h_out)
+        return LORA_ERR_BAD_SHAPE;
+    if (seg->P == 0) return LORA_OK;
+    if (!ws) return LORA_ERR_INVALID_ARG;
+    if (!aligned(ws, 16)) return LORA_ERR_MISALIGNED;
+    if (ws_bytes < lora_moe_ws_bytes(pool, seg->P)) return LORA_ERR_BUFFER_TOO_SMALL;
+    return LORA_OK;
+}
+
+int moe_shrink_checks(const lora_pool *pool, int which, const void *in, int64_t ld_in,
+                      const int32_t *token_of_pair)
+{
+    const lora_pool_desc &d = pool->d;
+    int rc = check_act(in, ld_in, d.proj[which == LORA_MOE_UPGATE ? 0 : 2].h_in, 2);
+    if (rc != LORA_OK) return rc;
+    if (which == LORA_MOE_UPGATE && !token_of_pair) return LORA_ERR_INVALID_ARG;
+    return LORA_OK;
+}
+
+int moe_expand_checks(const lora_pool *pool, int which, void *y0, void *y1, int64_t ldy)
+{
+    const lora_pool_desc &d = pool->d;
+    int rc = check_act(y0, ldy, d.proj[which == LORA_MOE_UPGATE ? 0 : 2].h_out, 2);
+    if (rc != LORA_OK) return rc;
+    if (which == LORA_MOE_UPGATE) return check_act(y1, ldy, d.proj[1].h_out, 2);
+    return LORA_OK;
+}
+
+int moe_shrink_launch(const lora_pool *pool, int layer, int which, const void *in, int64_t ld_in,
+                      const int32_t *token_of_pair, const lora_segments *seg, void *ws,
+                      hipStream_t st)
+{
+    float *v0 = static_cast<float *>(ws);
+    if (which == LORA_MOE_UPGATE) {
+        float *v1 = reinterpret_cast<float *>(static_cast<char *>(ws) + lora_v_bytes(pool, 0, seg->P));
+        return do_shrink(pool, layer, 0, 2, in, ld_in, token_of_pair, seg, v0, v1, st);
+    }
+    return do_shrink(pool, layer, 2, 1, in, ld_in, nullptr, seg, v0, nullptr, st);
+}
+
+int moe_expand_launch(const lora_pool *pool, int layer, int which, const lora_segments *seg,
+                      void *y0, void *y1, int64_t ldy, void *ws, hipStream_t st)
+{
+    const float *v0 = static_cast<const float *>(ws);
+    if (which == LORA_MOE_UPGATE) {
+        const float *v1 = reinterpret_cast<const float *>(static_cast<const char *>(ws) +
+                                                          lora_v_bytes(pool, 0, seg->P));
+        return do_expand(pool, layer, 0, 2, v0, v1, seg, y0, y1, ldy, LORA_DTYPE_BF16, st);
+    }
+    return do_expand(pool, layer, 2, 1, v0, nullptr, seg, y0, nullptr, ldy, LORA_DTYPE_BF16, st);
+}
+
+}  // namespace
+
+extern "C" {
+
+int lora_moe_shrink(const lora_pool *pool, int layer, int which, const void *in, int64_t ld_in,
+                    const int32_t *token_of_pair, const lora_segments *seg, void *ws,
+                    size_t ws_bytes, void *stream)
+{
+    int rc = moe_common_checks(pool, layer, which, seg, ws, ws_bytes);
+    if (rc != LORA_OK || seg->P == 0) return rc;
+    rc = moe_shrink_checks(pool, which, in, ld_in, token_of_pair);
+    if (rc != LORA_OK) return rc;
+    return moe_shrink_launch(pool, layer, which, in, ld_in, token_of_pair, seg, ws,
+                             static_cast<hipStream_t>(stream));
+}
+
+int lora_moe_expand(const lora_pool *pool, int layer, int which, const lora_segments *seg,
+                    void *y0, void *y1, int64_t ldy, void *ws, size_t ws_bytes, void *stream)
+{
+    int rc = moe_common_checks(pool, layer, which, seg, ws, ws_bytes);
+    if (rc != LORA_OK || seg->P == 0) return rc;
+    rc = moe_expand_checks(pool, which, y0, y1, ldy);
+    if (rc != LORA_OK) return rc;
+    return moe_expand_launch(pool, layer, which, seg, y0, y1, ldy, ws,
+                             static_cast<hipStream_t>(stream));
+}
+
+int lora_moe_apply(const lora_pool *pool, int layer, int which, const void *in, int64_t ld_in,
+                   const int32_t *token_of_pair, const lora_segments *seg, void *y0, void *y1,
+                   int64_t ldy, void *ws, size_t ws_bytes, void *stream)
+{
+    int rc = moe_common_checks(pool, layer, which, seg, ws, ws_bytes);
+    if (rc != LORA_OK || seg->P == 0) return rc;
+    rc = moe_shrink_checks(pool, which, in, ld_in, token_of_pair);
+    if (rc != LORA_OK) return rc;
+    rc = moe_expand_checks(pool, which, y0, y1, ldy);
+    if (rc != LORA_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    rc = moe_shrink_launch(pool, layer, which, in, ld_in, token_of_pair, seg, ws, st);
+    if (rc != LORA_OK) return rc;
+    return moe_expand_launch(pool, layer, which, seg, y0, y1, ldy, ws, st);
+}
+
+}  // extern "C"

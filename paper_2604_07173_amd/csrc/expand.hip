@@ -1,0 +1,231 @@
+// Expand with fused scale-and-accumulate: y[row] += scale * v[row] * B
+// (App. A.2.2 "expand phase"; Sec. 2.2: the update is added to the base output; Fig. 7b:
+// final addition of the two outputs).
+//
+// Work item = (row tile, projection, column slice).  The workgroup first adds the K parts
+// of the tile's v in a fixed order, applies the adapter's scale, and stages the result in
+// LDS as two bf16 planes hi + lo (hi = v truncated to bf16, lo = the rounded remainder), so
+// the MFMA sees v to about 16 mantissa bits although its operands are bf16.  Then every
+// wave walks over its 128-column chunks of the slice: it loads the chunk's packed B (16
+// bytes per lane, contiguous per wave) into operand registers once, and for each 16-row
+// sub-tile runs the MFMAs and read-modify-writes y.  The column permutation baked into the
+// packed B leaves each lane with eight consecutive output columns of a row, so the y access
+// is one 16-byte load and one 16-byte store per lane with 16 lanes covering 256 contiguous
+// bytes of a row.  B is read exactly once per (tile, chunk).
+#include "lora_internal.h"
+
+namespace lora {
+
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
+
+__device__ inline bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
+
+// fp32 -> bf16 bits, round to nearest even (NaN stays NaN)
+__device__ inline unsigned bf16_rne_bits(float f)
+{
+    unsigned u = __float_as_uint(f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (u >> 16) | 0x40u;
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+template <int R, bool F32>
+__global__ __launch_bounds__(256) void expand_kernel(ExpandParams p)
+{
+    constexpr int KS = R >= 32 ? R / 32 : 1;      // MFMA K steps over the rank
+    constexpr int TR = kTileRows;
+    constexpr int SUB = TR / 16;
+    constexpr int LD = R + 8;                     // padded LDS row (bf16 elements)
+    __shared__ __attribute__((aligned(16))) uint16_t v_hi[TR][LD];
+    __shared__ __attribute__((aligned(16))) uint16_t v_lo[TR][LD];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int g = lane >> 4, i16 = lane & 15;
+    const int n_tiles = p.counts[2];
+    const int per_tile = p.n_fused * p.n_slices;
+    const int n_items = n_tiles * per_tile;
+    const int groups = (p.n_chunks + p.waves - 1) / p.waves;        // chunk groups of a row
+    const int groups_per_slice = (groups + p.n_slices - 1) / p.n_slices;
+    const u32x4 zero4 = {0u, 0u, 0u, 0u};
+
+    for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
+        const int tile_ix = item / per_tile;
+        const int rem = item - tile_ix * per_tile;
+        const int pj = rem / p.n_slices;
+        const int slice = rem - pj * p.n_slices;
+        const lora_tile t = p.tiles[tile_ix];
+        const int nsub = (t.n_rows + 15) >> 4;
+        const Unit unit = p.units[(int64_t)t.key * p.n_proj + p.proj0 + pj];
+        const uint16_t *Bp = unit.B;
+        const float *vsrc = p.v[pj];
+
+        // ---- stage scale * sum_parts(v) as hi/lo bf16 planes -----------------------------
+        for (int o = tid; o < TR * (R / 4); o += blockDim.x) {
+            const int row = o / (R / 4);
+            const int j = (o - row * (R / 4)) * 4;
+            f32x4 s = {0.f, 0.f, 0.f, 0.f};
+            if (row < t.n_rows) {
+                const float *src = vsrc + ((int64_t)(t.row0 + row)) * R + j;
+                for (int part = 0; part < p.n_parts; ++part)
+                    s += *reinterpret_cast<const f32x4 *>(src + (int64_t)part * p.P * R);
+                s *= unit.scale;
+            }
+            unsigned hi[4], lo[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const unsigned u = __float_as_uint(s[q]) & 0xFFFF0000u;
+                hi[q] = u >> 16;
+                lo[q] = bf16_rne_bits(s[q] - __uint_as_float(u));
+            }
+            *reinterpret_cast<u32x2 *>(&v_hi[row][j]) = u32x2{hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16)};
+            *reinterpret_cast<u32x2 *>(&v_lo[row][j]) = u32x2{lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16)};
+        }
+        __syncthreads();
+
+        // destination rows of this lane: MFMA result register i holds row 4*g + i
+        int drow[SUB][4];
+#pragma unroll
+        for (int sub = 0; sub < SUB; ++sub)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int r = sub * 16 + g * 4 + i;
+                drow[sub][i] = r < t.n_rows ? p.perm[t.row0 + r] : -1;
+            }
+
+        const int cg_end = min((slice + 1) * groups_per_slice, groups);
+        for (int cg = slice * groups_per_slice; cg < cg_end; ++cg) {
+            const int chunk = cg * p.waves + wave;
+            if (chunk >= p.n_chunks) continue;                 // wave-uniform
+            const int col = chunk * kColChunk + i16 * 8;       // first of this lane's 8 columns
+            const bool col_ok = col < p.h_out;
+
+            // packed B of the chunk -> operand registers
+            u32x4 b[8][KS];
+#pragma unroll
+            for (int blk = 0; blk < 8; ++blk)
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    int64_t off;
+                    if (R >= 32) off = (((((int64_t)chunk * 8 + blk) * KS + ks) * 4 + g) * 16 + i16) * 8;
+                    else if (R == 16) off = ((((int64_t)chunk * 8 + blk) * 2 + (g & 1)) * 16 + i16) * 8;
+                    else off = (((int64_t)chunk * 8 + blk) * 16 + i16) * 8;
+                    b[blk][ks] = *reinterpret_cast<const u32x4 *>(Bp + off);
+                }
+
+#pragma unroll
+            for (int sub = 0; sub < SUB; ++sub) {
+                if (sub >= nsub) break;
+                // base output of this lane's rows (issued before the MFMAs)
+                u32x4 yv[4][F32 ? 2 : 1];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const bool ok = col_ok && drow[sub][i] >= 0;
+                    if (F32) {
+                        const float *yp = static_cast<const float *>(p.y[pj]) + (int64_t)drow[sub][i] * p.ldy + col;
+                        yv[i][0] = ok ? *reinterpret_cast<const u32x4 *>(yp) : zero4;
+                        yv[i][F32 ? 1 : 0] = ok ? *reinterpret_cast<const u32x4 *>(yp + 4) : zero4;
+                    } else {
+                        const uint16_t *yp = static_cast<const uint16_t *>(p.y[pj]) + (int64_t)drow[sub][i] * p.ldy + col;
+                        yv[i][0] = ok ? *reinterpret_cast<const u32x4 *>(yp) : zero4;
+                    }
+                }
+
+                // v operand of the sub-tile: row i16, K group g
+                const int row = sub * 16 + i16;
+                u32x4 a_hi[KS], a_lo[KS];
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    if (R >= 32) {
+                        a_hi[ks] = *reinterpret_cast<const u32x4 *>(&v_hi[row][ks * 32 + g * 8]);
+                        a_lo[ks] = *reinterpret_cast<const u32x4 *>(&v_lo[row][ks * 32 + g * 8]);
+                    } else if (R == 16) {
+                        // K = 32 holds hi (groups 0,1) and lo (groups 2,3) of the 16 rank entries
+                        a_hi[ks] = g < 2 ? *reinterpret_cast<const u32x4 *>(&v_hi[row][(g & 1) * 8])
+                                         : *reinterpret_cast<const u32x4 *>(&v_lo[row][(g & 1) * 8]);
+                        a_lo[ks] = zero4;
+                    } else {
+                        // K = 32 holds hi (group 0), lo (group 1), zeros (groups 2,3)
+                        a_hi[ks] = g == 0 ? *reinterpret_cast<const u32x4 *>(&v_hi[row][0])
+                                 : g == 1 ? *reinterpret_cast<const u32x4 *>(&v_lo[row][0]) : zero4;
+                        a_lo[ks] = zero4;
+                    }
+                }
+
+                f32x4 acc[8];
+#pragma unroll
+                for (int blk = 0; blk < 8; ++blk) {
+                    acc[blk] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int ks = 0; ks < KS; ++ks) {
+                        acc[blk] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                            as_bf16x8(a_hi[ks]), as_bf16x8(b[blk][ks]), acc[blk], 0, 0, 0);
+                        if (R >= 32)
+                            acc[blk] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                                as_bf16x8(a_lo[ks]), as_bf16x8(b[blk][ks]), acc[blk], 0, 0, 0);
+                    }
+                }
+
+                // y += delta: lane owns columns col .. col+7 of rows 4*g + i
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    if (!(col_ok && drow[sub][i] >= 0)) continue;
+                    if (F32) {
+                        float *yp = static_cast<float *>(p.y[pj]) + (int64_t)drow[sub][i] * p.ldy + col;
+                        f32x4 o0, o1;
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            o0[q] = __uint_as_float(yv[i][0][q]) + acc[q][i];
+                            o1[q] = __uint_as_float(yv[i][F32 ? 1 : 0][q]) + acc[4 + q][i];
+                        }
+                        *reinterpret_cast<f32x4 *>(yp) = o0;
+                        *reinterpret_cast<f32x4 *>(yp + 4) = o1;
+                    } else {
+                        uint16_t *yp = static_cast<uint16_t *>(p.y[pj]) + (int64_t)drow[sub][i] * p.ldy + col;
+                        u32x4 o;
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const unsigned u = yv[i][0][q];
+                            const float f0 = __uint_as_float(u << 16) + acc[2 * q][i];
+                            const float f1 = __uint_as_float(u & 0xFFFF0000u) + acc[2 * q + 1][i];
+                            o[q] = bf16_rne_bits(f0) | (bf16_rne_bits(f1) << 16);
+                        }
+                        *reinterpret_cast<u32x4 *>(yp) = o;
+                    }
+                }
+            }
+        }
+        __syncthreads();
+    }
+}
+
+template <int R>
+hipError_t launch_r(const ExpandParams &p, hipStream_t s)
+{
+    const dim3 block(p.waves * 64);
+    if (p.out_f32)
+        hipLaunchKernelGGL((expand_kernel<R, true>), dim3(p.grid), block, 0, s, p);
+    else
+        hipLaunchKernelGGL((expand_kernel<R, false>), dim3(p.grid), block, 0, s, p);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_expand(const ExpandParams &p, hipStream_t s)
+{
+    if (p.grid <= 0) return hipSuccess;
+    switch (p.rank) {
+    case 8: return launch_r<8>(p, s);
+    case 16: return launch_r<16>(p, s);
+    case 32: return launch_r<32>(p, s);
+    case 64: return launch_r<64>(p, s);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace lora

@@ -1,0 +1,114 @@
+// Internal declarations shared by the translation units of liblora (host side only;
+// kernels live in the .hip files and are reached through the launch_* functions).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/lora.h"
+
+namespace lora {
+
+// One entry of the device pointer table: 32 bytes, ordered [layer][adapter][expert][proj].
+struct Unit {
+    const uint16_t *A;  // packed shrink operand of the unit
+    const uint16_t *B;  // packed expand operand of the unit
+    float scale;        // the adapter's scale
+    int32_t rank;       // the adapter's own rank (<= pool rank; the rest is zero padding)
+    int32_t pad[2];
+};
+static_assert(sizeof(Unit) == 32, "table entry is 32 bytes");
+
+constexpr int kTileRows = 32;        // rows per tile handed to the kernels
+constexpr int kKBlock = 32;          // K elements per MFMA step (v_mfma_f32_16x16x32_bf16)
+constexpr int kColChunk = 128;       // output columns one wave owns in expand
+constexpr int kPartKBlocks = 32;     // K-blocks one shrink workgroup reduces (1024 inputs)
+constexpr int kMaxParts = 64;
+
+// ---- packed layout sizes ---------------------------------------------------------------
+inline int kblocks_of(int h_in) { return (h_in + kKBlock - 1) / kKBlock; }
+inline int chunks_of(int h_out) { return (h_out + kColChunk - 1) / kColChunk; }
+inline size_t packed_A_bytes(int h_in, int rank) { return (size_t)kblocks_of(h_in) * kKBlock * rank * 2; }
+inline size_t packed_B_bytes(int h_out, int rank) { return (size_t)chunks_of(h_out) * kColChunk * rank * 2; }
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// ---- launch parameter blocks -----------------------------------------------------------
+struct PackParams {
+    const uint16_t *src;     // first unit's row-major matrix
+    int64_t src_stride;      // elements between consecutive units' matrices
+    uint16_t *dst;           // first unit's packed destination
+    int64_t dst_stride;      // elements between consecutive units' packed matrices
+    int n_units;
+    int h;                   // h_in (A) or h_out (B)
+    int rank;                // pool rank
+    int src_rank;            // rank of the source matrices (<= rank)
+};
+
+struct SegParams {
+    const int32_t *adapter_id;
+    const int32_t *expert_id;
+    int P;
+    int n_adapters;
+    int n_experts;
+    int tile_rows;
+    int passes;              // radix passes of 8 bits over the key
+    int32_t *perm;
+    int32_t *seg_start;
+    int32_t *seg_key;
+    lora_tile *tiles;
+    int32_t *counts;
+    uint32_t *status;
+};
+
+struct ShrinkParams {
+    const Unit *units;       // table rows of the layer
+    int n_proj;              // projections per unit (table stride)
+    int proj0;               // first projection handled
+    int n_fused;             // 1 or 2 projections sharing x
+    const uint16_t *x;
+    int64_t ldx;
+    const int32_t *src_row;  // may be null
+    const int32_t *perm;
+    const lora_tile *tiles;
+    const int32_t *counts;
+    float *v[2];             // per fused projection: [n_parts][P][rank]
+    int P;
+    int h_in;
+    int n_parts;
+    int kb_per_part;
+    int rank;
+    int grid;
+};
+
+struct ExpandParams {
+    const Unit *units;
+    int n_proj;
+    int proj0;
+    int n_fused;
+    const float *v[2];
+    int n_parts;
+    int P;
+    const int32_t *perm;
+    const lora_tile *tiles;
+    const int32_t *counts;
+    void *y[2];
+    int64_t ldy;
+    int h_out;
+    int n_chunks;            // 128-column chunks
+    int n_slices;            // workgroups per (tile, projection)
+    int waves;               // waves per workgroup
+    int out_f32;
+    int rank;
+    int grid;
+};
+
+hipError_t launch_pack_A(const PackParams &p, hipStream_t s);
+hipError_t launch_pack_B(const PackParams &p, hipStream_t s);
+hipError_t launch_unpack_A(const PackParams &p, hipStream_t s);   // src = packed, dst = row-major
+hipError_t launch_unpack_B(const PackParams &p, hipStream_t s);
+hipError_t launch_segments(const SegParams &p, hipStream_t s);
+hipError_t launch_shrink(const ShrinkParams &p, hipStream_t s);
+hipError_t launch_expand(const ExpandParams &p, hipStream_t s);
+
+}  // namespace lora

@@ -1,0 +1,50 @@
+// Packed (re-tiled) storage of a unit's A and B inside the pool slab.
+//
+// The kernels feed v_mfma_f32_16x16x32_bf16, whose two bf16 operands want, per lane
+// l = 16*g + i (g = 0..3, i = 0..15), eight consecutive K elements 8*g .. 8*g+7 of
+// row/column i.  Storing the matrices so that lane l's eight values are contiguous and
+// consecutive lanes are adjacent lets one 16-byte load per lane fetch an operand with the
+// whole wave reading one contiguous 1 KiB block.
+//
+// Shrink operand, A[h_in][rank] (K = input index c, M = rank index j):
+//   rank >= 16: block (kb = c/32, nb = j/16) of 64 lanes x 8 values;
+//               lane 16*g + (j%16) holds c = 32*kb + 8*g + t, t = 0..7.
+//   rank == 8 : block kb of 32 lanes x 8 values; lane 8*g + j holds c = 32*kb + 8*g + t.
+//   K is padded with zeros to a multiple of 32.
+//
+// Expand operand, B[rank][h_out] (K = rank index j, N = output column d):
+//   columns are grouped in chunks of 128; inside a chunk the MFMA column slot n = 0..15 of
+//   sub-block blk = 0..7 is output column 8*n + blk, so that after the eight MFMAs of a
+//   chunk a lane owns eight consecutive output columns of a row (one 16-byte access).
+//   K steps of 32: ks = j/32; within a step lane group gl = (j%32)/8, t = j%8; only
+//   G = min(rank, 32)/8 lane groups are stored.
+//   Columns are padded with zeros to a multiple of 128.
+#pragma once
+#include <stdint.h>
+
+#ifndef LORA_HD
+#define LORA_HD __host__ __device__ inline
+#endif
+
+namespace lora {
+
+LORA_HD int64_t packA_index(int c, int j, int rank)
+{
+    const int kb = c >> 5, g = (c & 31) >> 3, t = c & 7;
+    if (rank == 8) return (((int64_t)kb * 32) + g * 8 + j) * 8 + t;
+    const int NB = rank >> 4, nb = j >> 4, n = j & 15;
+    return ((((int64_t)kb * NB + nb) * 64) + g * 16 + n) * 8 + t;
+}
+
+LORA_HD int packB_ksteps(int rank) { return rank >= 32 ? rank / 32 : 1; }
+LORA_HD int packB_groups(int rank) { return rank >= 32 ? 4 : rank / 8; }
+
+LORA_HD int64_t packB_index(int j, int d, int rank)
+{
+    const int chunk = d >> 7, dd = d & 127, n = dd >> 3, blk = dd & 7;
+    const int KS = packB_ksteps(rank), G = packB_groups(rank);
+    const int ks = j >> 5, gl = (j & 31) >> 3, t = j & 7;
+    return ((((((int64_t)chunk * 8 + blk) * KS + ks) * G + gl) * 16) + n) * 8 + t;
+}
+
+}  // namespace lora

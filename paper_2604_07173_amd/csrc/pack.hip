@@ -1,0 +1,84 @@
+// Repacking of row-major A[h_in][r] / B[r][h_out] into the pool's tiled storage and back.
+// One thread moves one 16-byte group (eight values that differ only in their K offset t).
+#include "lora_internal.h"
+#include "lora_layout.h"
+
+namespace lora {
+
+// direction: 0 = row-major -> packed, 1 = packed -> row-major (padding is dropped)
+template <int DIR>
+__global__ __launch_bounds__(256) void pack_A_kernel(PackParams p)
+{
+    const int kblocks = (p.h + 31) / 32;
+    const int64_t groups = (int64_t)kblocks * 4 * p.rank;     // (kb, g, j)
+    const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (gid >= groups) return;
+    const int unit = blockIdx.y;
+    const int j = (int)(gid % p.rank);
+    const int g = (int)((gid / p.rank) & 3);
+    const int kb = (int)(gid / ((int64_t)p.rank * 4));
+    const int c0 = kb * 32 + g * 8;
+    uint16_t *packed = (DIR == 0 ? p.dst : const_cast<uint16_t *>(p.src)) +
+                       (int64_t)unit * (DIR == 0 ? p.dst_stride : p.src_stride) +
+                       packA_index(c0, j, p.rank);
+    uint16_t *plain = (DIR == 0 ? const_cast<uint16_t *>(p.src) : p.dst) +
+                      (int64_t)unit * (DIR == 0 ? p.src_stride : p.dst_stride);
+    for (int t = 0; t < 8; ++t) {
+        const int c = c0 + t;
+        const bool in = c < p.h && j < p.src_rank;
+        if (DIR == 0) packed[t] = in ? plain[(int64_t)c * p.src_rank + j] : (uint16_t)0;
+        else if (in) plain[(int64_t)c * p.src_rank + j] = packed[t];
+    }
+}
+
+template <int DIR>
+__global__ __launch_bounds__(256) void pack_B_kernel(PackParams p)
+{
+    const int chunks = (p.h + 127) / 128;
+    const int jg = p.rank / 8;                                 // groups of 8 rank indices
+    const int64_t groups = (int64_t)chunks * 128 * jg;         // (d, j/8)
+    const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (gid >= groups) return;
+    const int unit = blockIdx.y;
+    const int d = (int)(gid % ((int64_t)chunks * 128));
+    const int j0 = (int)(gid / ((int64_t)chunks * 128)) * 8;
+    uint16_t *packed = (DIR == 0 ? p.dst : const_cast<uint16_t *>(p.src)) +
+                       (int64_t)unit * (DIR == 0 ? p.dst_stride : p.src_stride) +
+                       packB_index(j0, d, p.rank);
+    uint16_t *plain = (DIR == 0 ? const_cast<uint16_t *>(p.src) : p.dst) +
+                      (int64_t)unit * (DIR == 0 ? p.src_stride : p.dst_stride);
+    for (int t = 0; t < 8; ++t) {
+        const int j = j0 + t;
+        const bool in = d < p.h && j < p.src_rank;
+        if (DIR == 0) packed[t] = in ? plain[(int64_t)j * p.h + d] : (uint16_t)0;
+        else if (in) plain[(int64_t)j * p.h + d] = packed[t];
+    }
+}
+
+template <typename K>
+static hipError_t launch_pack(K kernel, const PackParams &p, int64_t groups, hipStream_t s)
+{
+    if (p.n_units <= 0 || groups <= 0) return hipSuccess;
+    dim3 grid((unsigned)((groups + 255) / 256), (unsigned)p.n_units);
+    hipLaunchKernelGGL(kernel, grid, dim3(256), 0, s, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_pack_A(const PackParams &p, hipStream_t s)
+{
+    return launch_pack(pack_A_kernel<0>, p, (int64_t)kblocks_of(p.h) * 4 * p.rank, s);
+}
+hipError_t launch_unpack_A(const PackParams &p, hipStream_t s)
+{
+    return launch_pack(pack_A_kernel<1>, p, (int64_t)kblocks_of(p.h) * 4 * p.rank, s);
+}
+hipError_t launch_pack_B(const PackParams &p, hipStream_t s)
+{
+    return launch_pack(pack_B_kernel<0>, p, (int64_t)chunks_of(p.h) * 128 * (p.rank / 8), s);
+}
+hipError_t launch_unpack_B(const PackParams &p, hipStream_t s)
+{
+    return launch_pack(pack_B_kernel<1>, p, (int64_t)chunks_of(p.h) * 128 * (p.rank / 8), s);
+}
+
+}  // namespace lora

@@ -1,0 +1,73 @@
+"""Helpers shared by the GPU parity tests (not a test module)."""
+from __future__ import annotations
+
+from typing import Optional
+
+import numpy as np
+
+import workloads as W
+from oracle import lora_oracle as O
+
+REL_FRO = 5e-3     # relative Frobenius error bound of the delta (bf16 in, fp32 accumulate)
+MAX_ABS = 2e-2     # absolute bound on any element of the delta
+
+
+def oracle_projection(b: W.Batch, ws: W.WeightSource, layer: int, j: int,
+                      rows: Optional[np.ndarray] = None, use_y: bool = True):
+    """fp64 oracle of projection j over all rows or a sample of them."""
+    w = b.workload
+    p = w.projs[j]
+    x = b.inputs[p.input]
+    aid = b.adapter_id
+    eid = b.expert_id
+    src = None if p.input == "mid" else b.token_of_pair
+    y = b.y_in[p.name] if use_y else None
+    if rows is not None:
+        aid = aid[rows]
+        eid = None if eid is None else eid[rows]
+        src = rows.astype(np.int32) if src is None else src[rows]
+        y = None if y is None else np.ascontiguousarray(y[rows])
+    n_units = w.n_adapters * w.n_experts
+    A_units = [None] * n_units
+    B_units = [None] * n_units
+    e_arr = eid if eid is not None else np.zeros_like(aid)
+    for a, e in set(zip(aid[aid >= 0].tolist(), e_arr[aid >= 0].tolist())):
+        if 0 <= a < w.n_adapters and 0 <= e < w.n_experts:
+            A, B = ws.unit_arrays(a, layer, e, j)
+            A_units[a * w.n_experts + e] = np.ascontiguousarray(A)
+            B_units[a * w.n_experts + e] = np.ascontiguousarray(B)
+    if all(u is None for u in A_units):   # no active row: any unit defines the shapes
+        A, B = ws.unit_arrays(0, layer, 0, j)
+        A_units[0], B_units[0] = np.ascontiguousarray(A), np.ascontiguousarray(B)
+    return O.delta(x, aid, A_units, B_units, b.scale, n_adapters=w.n_adapters,
+                   n_experts=w.n_experts, expert_id=eid, src_row=src, y_in=y)
+
+
+def bf16_order(bits: np.ndarray) -> np.ndarray:
+    """Map bf16 bit patterns to integers whose difference counts representable steps."""
+    b = bits.astype(np.int64)
+    mag = b & 0x7FFF
+    return np.where(b & 0x8000, -mag, mag)
+
+
+def check_delta(got_f64: np.ndarray, want_delta: np.ndarray, what: str = ""):
+    """The tolerance of the floating-point path: relative Frobenius <= 5e-3, max abs <= 2e-2."""
+    diff = got_f64 - want_delta
+    den = np.linalg.norm(want_delta)
+    rel = np.linalg.norm(diff) / den if den > 0 else np.linalg.norm(diff)
+    mx = float(np.max(np.abs(diff))) if diff.size else 0.0
+    assert rel <= REL_FRO, f"{what}: rel Frobenius {rel:.3e} > {REL_FRO}"
+    assert mx <= MAX_ABS, f"{what}: max abs {mx:.3e} > {MAX_ABS}"
+    return rel, mx
+
+
+def check_accumulate(got_bits: np.ndarray, res, what: str = ""):
+    """Accumulate mode: every element within one bf16 step of the oracle's once-rounded sum,
+    and the whole output within the Frobenius bound of the unrounded sum."""
+    steps = np.abs(bf16_order(got_bits) - bf16_order(res.y_bf16))
+    assert steps.max(initial=0) <= 1, f"{what}: {int((steps > 1).sum())} elements off by >1 bf16 step"
+    got = W.bf16_bits_to_f32(got_bits).astype(np.float64)
+    den = np.linalg.norm(res.y_out)
+    rel = np.linalg.norm(got - res.y_out) / den if den > 0 else 0.0
+    assert rel <= REL_FRO, f"{what}: rel Frobenius of y {rel:.3e}"
+    return int(steps.max(initial=0)), rel

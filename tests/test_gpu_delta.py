@@ -1,0 +1,245 @@
+"""Shrink / expand / MoE application against the fp64 oracle, element by element, at sizes
+that span several tiles, K parts and column chunks with ragged tails."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2604_07173_amd as L
+import workloads as W
+from gpu_common import check_accumulate, check_delta, oracle_projection
+from paper_2604_07173_amd.harness import DeviceBatch, DevicePool, LayerRunner, bits_from_dev, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def dense_workload(rank, h_in, h_out, n=5, tokens=70, ids="uniform", alpha=0.0):
+    return W.Workload("t", "dense", n, 1, 1, rank, (W.Proj("p", h_in, h_out, "x"),), tokens, ids,
+                      alpha)
+
+
+def moe_workload(rank, h, f, n=6, E=4, k=2, tokens=40, alpha=1.0):
+    projs = (W.Proj("gate", h, f, "x"), W.Proj("up", h, f, "x"), W.Proj("down", f, h, "mid"))
+    return W.Workload("t", "moe", n, E, k, rank, projs, tokens, "zipf", alpha)
+
+
+def run_dense(w, seed, y_mode, out_f32=False, drop=0.0, hetero=True, n_layers=1, layer=0):
+    b = W.make_batch(w, seed, y_mode=y_mode, no_adapter_frac=drop, hetero_scale=hetero)
+    ws = W.make_weights(w, seed, n_layers=n_layers, bank_elems=1 << 20)
+    dp = DevicePool(ws, b.scale)
+    db = DeviceBatch(b)
+    run = LayerRunner(dp, db)
+    run.build_segments()
+    p = w.projs[0]
+    x = db.inputs["x"]
+    L.lora_shrink(dp.pool, layer, 0, x, x.shape[1], None, db.seg, run.v)
+    if out_f32:
+        y = torch.from_numpy(W.bf16_bits_to_f32(b.y_in["p"])).cuda()
+        L.lora_expand(dp.pool, layer, 0, run.v, db.seg, y, y.shape[1], L.LORA_DTYPE_F32)
+        torch.cuda.synchronize()
+        got = y.cpu().numpy().astype(np.float64)
+    else:
+        y = db.y["p"]
+        L.lora_expand(dp.pool, layer, 0, run.v, db.seg, y, y.shape[1], L.LORA_DTYPE_BF16)
+        torch.cuda.synchronize()
+        got = bits_from_dev(y)
+    return b, ws, got, (dp, db, run)
+
+
+SHAPES = [(8, 200, 328), (16, 200, 328), (32, 72, 136), (64, 264, 520), (16, 1024, 1024),
+          (8, 40, 8), (16, 8, 1032)]
+
+
+@pytest.mark.parametrize("rank,h_in,h_out", SHAPES)
+def test_delta_mode_bf16(rank, h_in, h_out):
+    w = dense_workload(rank, h_in, h_out)
+    b, ws, got, _ = run_dense(w, 11, "zero")
+    res = oracle_projection(b, ws, 0, 0)
+    check_delta(W.bf16_bits_to_f32(got).astype(np.float64), res.delta, f"r{rank} {h_in}x{h_out}")
+
+
+@pytest.mark.parametrize("rank,h_in,h_out", SHAPES)
+def test_delta_mode_f32_output(rank, h_in, h_out):
+    w = dense_workload(rank, h_in, h_out)
+    b, ws, got, _ = run_dense(w, 12, "zero", out_f32=True)
+    res = oracle_projection(b, ws, 0, 0)
+    rel, _ = check_delta(got, res.delta, f"r{rank} {h_in}x{h_out} f32")
+    assert rel < 1e-4     # fp32 output: only the accumulation order and the hi/lo split remain
+
+
+@pytest.mark.parametrize("rank,h_in,h_out", SHAPES)
+def test_accumulate_mode_and_untouched_rows(rank, h_in, h_out):
+    w = dense_workload(rank, h_in, h_out)
+    b, ws, got, _ = run_dense(w, 13, "normal", drop=0.25)
+    res = oracle_projection(b, ws, 0, 0)
+    check_accumulate(got, res, f"r{rank} {h_in}x{h_out}")
+    none = b.adapter_id < 0
+    assert none.any()
+    assert np.array_equal(got[none], b.y_in["p"][none])      # rows without adapter: bit-identical
+
+
+def test_f32_accumulate_keeps_base():
+    w = dense_workload(16, 136, 264)
+    b, ws, got, _ = run_dense(w, 14, "normal", out_f32=True, drop=0.2)
+    res = oracle_projection(b, ws, 0, 0)
+    np.testing.assert_allclose(got, res.y_out, rtol=0, atol=2e-5 * max(1.0, np.abs(res.y_out).max()))
+    none = b.adapter_id < 0
+    assert np.array_equal(got[none], W.bf16_bits_to_f32(b.y_in["p"][none]).astype(np.float64))
+
+
+@pytest.mark.parametrize("tokens", [1, 15, 16, 17, 31, 32, 33, 64, 65, 130])
+def test_segment_lengths_around_tile_boundaries(tokens):
+    """One adapter only: the segment has exactly `tokens` rows (1 .. several 32-row tiles)."""
+    w = dense_workload(16, 264, 392, n=1, tokens=tokens)
+    b, ws, got, _ = run_dense(w, 15, "normal")
+    res = oracle_projection(b, ws, 0, 0)
+    check_accumulate(got, res, f"{tokens} rows")
+
+
+def test_shrink_output_matches_oracle_v_and_src_row():
+    w = dense_workload(16, 2080, 136, n=4, tokens=72)
+    b = W.make_batch(w, 16, hetero_scale=True)
+    ws = W.make_weights(w, 16, bank_elems=1 << 20)
+    dp, db = DevicePool(ws, b.scale), DeviceBatch(b)
+    run = LayerRunner(dp, db)
+    run.build_segments()
+    rng = np.random.default_rng(16)
+    src = rng.integers(0, 72, size=72).astype(np.int32)
+    x = db.inputs["x"]
+    L.lora_shrink(dp.pool, 0, 0, x, x.shape[1], to_dev(src), db.seg, run.v)
+    torch.cuda.synchronize()
+    P, r = 72, 16
+    n_parts = L.lora_v_bytes(dp.pool, 0, P) // (P * r * 4)
+    assert n_parts >= 2      # 2080 inputs: more than one K part
+    v = run.v.cpu().numpy()[:n_parts * P * r].reshape(n_parts, P, r).astype(np.float64).sum(0)
+    b.token_of_pair = src
+    res = oracle_projection(b, ws, 0, 0)
+    perm = db.seg.perm.cpu().numpy()[:int(db.seg.counts.cpu()[1])]
+    np.testing.assert_allclose(v[:len(perm)], res.v[perm], rtol=1e-5, atol=1e-5)
+
+
+def test_leading_dimensions_larger_than_widths():
+    w = dense_workload(16, 200, 136, tokens=50)
+    b = W.make_batch(w, 17, y_mode="normal")
+    ws = W.make_weights(w, 17, bank_elems=1 << 20)
+    dp, db = DevicePool(ws, b.scale), DeviceBatch(b)
+    run = LayerRunner(dp, db)
+    run.build_segments()
+    xpad = torch.full((50, 216), 0x7FC0, dtype=torch.int16, device="cuda")   # NaN padding
+    xpad[:, :200] = db.inputs["x"]
+    ypad = torch.full((50, 160), 0x1234, dtype=torch.int16, device="cuda")
+    ypad[:, :136] = db.y["p"]
+    L.lora_shrink(dp.pool, 0, 0, xpad, 216, None, db.seg, run.v)
+    L.lora_expand(dp.pool, 0, 0, run.v, db.seg, ypad, 160, L.LORA_DTYPE_BF16)
+    torch.cuda.synchronize()
+    got = bits_from_dev(ypad)
+    assert (got[:, 136:] == 0x1234).all()
+    check_accumulate(np.ascontiguousarray(got[:, :136]), oracle_projection(b, ws, 0, 0), "ld")
+
+
+def test_tiny_integer_cases_are_bit_exact():
+    """Small integer inputs: every product and sum is exact in fp32 and bf16, so the GPU
+    output must equal the oracle bit for bit."""
+    rng = np.random.default_rng(18)
+    w = W.Workload("t", "moe", 2, 2, 1, 8, (W.Proj("gate", 8, 8, "x"), W.Proj("up", 8, 8, "x"),
+                                            W.Proj("down", 8, 8, "mid")), 4, "uniform")
+    for trial in range(4):
+        b = W.make_batch(w, 100 + trial, y_mode="normal", no_adapter_frac=0.3)
+        ints = lambda shape: W.f32_to_bf16_bits(rng.integers(-3, 4, size=shape).astype(np.float32))
+        b.inputs = {"x": ints((4, 8)), "mid": ints((4, 8))}
+        b.y_in = {k: ints((4, 8)) for k in ("gate", "up", "down")}
+        b.scale = np.array([0.5, 2.0], np.float32)
+        ws = W.make_weights(w, 100 + trial, bank_elems=1 << 16)
+        ws.bank[:] = ints(ws.bank.shape)
+        dp, db = DevicePool(ws, b.scale), DeviceBatch(b)
+        LayerRunner(dp, db).step(0)
+        torch.cuda.synchronize()
+        for j, p in enumerate(w.projs):
+            res = oracle_projection(b, ws, 0, j)
+            assert np.array_equal(bits_from_dev(db.y[p.name]), res.y_bf16), (trial, p.name)
+
+
+@pytest.mark.parametrize("rank,h,f,E,k,tokens", [(16, 264, 392, 4, 2, 40), (8, 136, 776, 8, 4, 33),
+                                                 (64, 136, 264, 2, 2, 50), (32, 72, 136, 3, 1, 20)])
+def test_moe_apply_matches_oracle(rank, h, f, E, k, tokens):
+    w = moe_workload(rank, h, f, E=E, k=k, tokens=tokens)
+    b = W.make_batch(w, 19, y_mode="normal", no_adapter_frac=0.1, hetero_scale=True)
+    ws = W.make_weights(w, 19, n_layers=2, bank_elems=1 << 21)
+    dp, db = DevicePool(ws, b.scale), DeviceBatch(b)
+    run = LayerRunner(dp, db)
+    run.step(1)                      # second layer of the pool
+    torch.cuda.synchronize()
+    for j, p in enumerate(w.projs):
+        res = oracle_projection(b, ws, 1, j)
+        got = bits_from_dev(db.y[p.name])
+        check_accumulate(got, res, f"moe {p.name}")
+        none = b.adapter_id < 0
+        assert np.array_equal(got[none], b.y_in[p.name][none])
+    # delta mode on the same batch
+    b0 = W.make_batch(w, 19, y_mode="zero", no_adapter_frac=0.1, hetero_scale=True)
+    db0 = DeviceBatch(b0)
+    LayerRunner(dp, db0).step(1)
+    torch.cuda.synchronize()
+    for j, p in enumerate(w.projs):
+        res = oracle_projection(b0, ws, 1, j)
+        check_delta(W.bf16_bits_to_f32(bits_from_dev(db0.y[p.name])).astype(np.float64), res.delta,
+                    f"moe delta {p.name}")
+
+
+def test_results_are_bit_identical_run_to_run():
+    w = moe_workload(16, 520, 264, E=4, k=2, tokens=200)
+    b = W.make_batch(w, 20, y_mode="normal")
+    ws = W.make_weights(w, 20, bank_elems=1 << 21)
+    dp = DevicePool(ws, b.scale)
+    outs = []
+    for _ in range(3):
+        db = DeviceBatch(b)
+        LayerRunner(dp, db).step(0)
+        torch.cuda.synchronize()
+        outs.append({k: v.clone() for k, v in db.y.items()})
+    for k in outs[0]:
+        assert torch.equal(outs[0][k], outs[1][k]) and torch.equal(outs[0][k], outs[2][k])
+
+
+def test_row_permutation_invariance_on_gpu():
+    """Sec. 2.2: each row's update is independent of the batch it travels in."""
+    w = dense_workload(16, 264, 136, n=4, tokens=90)
+    b = W.make_batch(w, 21, y_mode="normal", no_adapter_frac=0.1)
+    ws = W.make_weights(w, 21, bank_elems=1 << 20)
+    dp = DevicePool(ws, b.scale)
+    db = DeviceBatch(b)
+    LayerRunner(dp, db).step(0)
+    perm = np.random.default_rng(21).permutation(90)
+    b2 = W.Batch(w, b.adapter_id[perm], None, b.token_of_pair.copy(),
+                 {"x": np.ascontiguousarray(b.inputs["x"][perm])},
+                 {"p": np.ascontiguousarray(b.y_in["p"][perm])}, b.scale)
+    db2 = DeviceBatch(b2)
+    LayerRunner(dp, db2).step(0)
+    torch.cuda.synchronize()
+    a, c = bits_from_dev(db.y["p"]), bits_from_dev(db2.y["p"])
+    # rows of a segment are summed independently, so even the bits agree
+    assert np.array_equal(a[perm], c)
+
+
+def test_argument_errors_on_the_device_path():
+    w = dense_workload(16, 200, 136, tokens=20)
+    b = W.make_batch(w, 22)
+    ws = W.make_weights(w, 22, bank_elems=1 << 20)
+    dp, db = DevicePool(ws, b.scale), DeviceBatch(b)
+    run = LayerRunner(dp, db)
+    x = db.inputs["x"]
+    with pytest.raises(L.LoraError) as e:      # segments not built yet
+        L.lora_shrink(dp.pool, 0, 0, x, 200, None, db.seg, run.v)
+    assert e.value.status == -5
+    run.build_segments()
+    for args, status in [((1, 0, x, 200), -2), ((0, 1, x, 200), -2), ((0, 0, x, 192), -2),
+                         ((0, 0, x, 204), -2), ((0, 0, x.data_ptr() + 2, 200), -7),
+                         ((0, 0, None, 200), -1)]:
+        with pytest.raises(L.LoraError) as e:
+            L.lora_shrink(dp.pool, args[0], args[1], args[2], args[3], None, db.seg, run.v)
+        assert e.value.status == status, args
+    with pytest.raises(L.LoraError) as e:
+        L.lora_expand(dp.pool, 0, 0, run.v, db.seg, db.y["p"], 136, 7)
+    assert e.value.status == -1
+    with pytest.raises(L.LoraError) as e:
+        L.lora_moe_apply(dp.pool, 0, 0, x, 200, None, db.seg, db.y["p"], db.y["p"], 136, run.v)
+    assert e.value.status == -2            # not a three-projection pool

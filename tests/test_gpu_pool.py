@@ -1,0 +1,108 @@
+"""Adapter pool and pointer table: repacking is a bit-exact permutation, the device table
+points where the host layout says, both loading routes fill the slab identically."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2604_07173_amd as L
+import workloads as W
+from paper_2604_07173_amd.harness import DevicePool, bits_from_dev, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def small_workload(rank, E=2, n=3, h_in=72, h_out=200):
+    projs = (W.Proj("gate", h_in, h_out, "x"), W.Proj("up", h_in, h_out, "x"),
+             W.Proj("down", h_out, h_in, "mid"))
+    return W.Workload("t", "moe", n, E, 2, rank, projs, 16, "uniform")
+
+
+@pytest.mark.parametrize("rank", [8, 16, 32, 64])
+def test_pack_unpack_roundtrip_is_bit_exact(rank):
+    w = small_workload(rank)
+    ws = W.make_weights(w, 5, n_layers=2, bank_elems=1 << 18)
+    dp = DevicePool(ws, np.ones(w.n_adapters, np.float32))
+    for a in range(w.n_adapters):
+        for layer in range(2):
+            for e in range(w.n_experts):
+                for j, p in enumerate(w.projs):
+                    A_out = torch.full((p.h_in, rank), -1, dtype=torch.int16, device="cuda")
+                    B_out = torch.full((rank, p.h_out), -1, dtype=torch.int16, device="cuda")
+                    L.lora_pool_read_unit(dp.pool, a, layer, e, j, A_out, B_out)
+                    torch.cuda.synchronize()
+                    A, B = ws.unit_arrays(a, layer, e, j)
+                    assert np.array_equal(bits_from_dev(A_out), A)
+                    assert np.array_equal(bits_from_dev(B_out), B)
+
+
+def test_device_table_matches_host_layout():
+    w = small_workload(16)
+    ws = W.make_weights(w, 6, n_layers=2, bank_elems=1 << 18)
+    scale = np.array([0.5, 1.0, 1.5], np.float32)
+    dp = DevicePool(ws, scale)
+    n_entries = 2 * w.n_adapters * w.n_experts * 3
+    raw = dp.slab[:n_entries * 32].cpu().numpy()
+    ent = raw.view(np.dtype([("A", "<u8"), ("B", "<u8"), ("scale", "<f4"), ("rank", "<i4"),
+                             ("pad", "<i4", 2)]))
+    base = dp.slab.data_ptr()
+    seen = set()
+    i = 0
+    for layer in range(2):
+        for a in range(w.n_adapters):
+            for e in range(w.n_experts):
+                for j in range(3):
+                    lay = L.lora_pool_unit_layout(dp.pool, a, layer, e, j)
+                    assert ent["A"][i] == base + lay["A_offset"]
+                    assert ent["B"][i] == base + lay["B_offset"]
+                    assert ent["scale"][i] == scale[a] and ent["rank"][i] == 16
+                    assert lay["A_offset"] % 256 == 0 and lay["B_offset"] % 256 == 0
+                    assert lay["A_offset"] + lay["A_bytes"] <= dp.nbytes
+                    assert lay["B_offset"] + lay["B_bytes"] <= dp.nbytes
+                    for lo, n in ((lay["A_offset"], lay["A_bytes"]), (lay["B_offset"], lay["B_bytes"])):
+                        assert not any(lo < hi2 and lo2 < lo + n for lo2, hi2 in seen)
+                        seen.add((lo, lo + n))
+                    i += 1
+
+
+def test_register_with_pointer_arrays_equals_layerwise_loading():
+    w = small_workload(8, E=2, n=2)
+    ws = W.make_weights(w, 7, n_layers=1, bank_elems=1 << 18)
+    dp = DevicePool(ws, np.ones(2, np.float32))
+    desc = L.PoolDesc(2, 1, 2, [(p.h_in, p.h_out) for p in w.projs], 8, scale=[1.0, 1.0])
+    slab = torch.zeros(L.lora_pool_bytes(desc), dtype=torch.uint8, device="cuda")
+    keep, A_src, B_src = [], [], []
+    for a in range(2):
+        for e in range(2):
+            for j in range(3):
+                A, B = ws.unit_arrays(a, 0, e, j)
+                tA, tB = to_dev(np.ascontiguousarray(A)), to_dev(np.ascontiguousarray(B))
+                keep += [tA, tB]
+                A_src.append(tA)
+                B_src.append(tB)
+    pool = L.lora_register_pool(desc, slab, A_src=A_src, B_src=B_src)
+    torch.cuda.synchronize()
+    n_table = 2 * 2 * 3 * 32
+    # tables differ only in the absolute addresses; packed data must be identical
+    assert torch.equal(slab[256 * ((n_table + 255) // 256):], dp.slab[256 * ((n_table + 255) // 256):])
+    del pool
+
+
+def test_lower_adapter_rank_is_zero_padded():
+    w = small_workload(16, E=1, n=2)
+    w4 = W.scaled(w, rank=8)           # source matrices of rank 8 inside a rank-16 pool
+    ws = W.make_weights(w4, 8, n_layers=1, bank_elems=1 << 18)
+    desc = L.PoolDesc(2, 1, 1, [(p.h_in, p.h_out) for p in w.projs], 16, adapter_rank=[8, 8])
+    slab = torch.empty(L.lora_pool_bytes(desc), dtype=torch.uint8, device="cuda")
+    pool = L.lora_register_pool(desc, slab)
+    bank = to_dev(ws.bank)
+    for a in range(2):
+        L.lora_pool_load_adapter_layer(pool, a, 0, bank.data_ptr() + 2 * int(ws.window[a, 0]))
+    p = w.projs[0]
+    A_out = torch.full((p.h_in, 16), -1, dtype=torch.int16, device="cuda")
+    B_out = torch.full((16, p.h_out), -1, dtype=torch.int16, device="cuda")
+    L.lora_pool_read_unit(pool, 1, 0, 0, 0, A_out, B_out)
+    torch.cuda.synchronize()
+    A, B = ws.unit_arrays(1, 0, 0, 0)
+    assert np.array_equal(bits_from_dev(A_out)[:, :8], A) and not bits_from_dev(A_out)[:, 8:].any()
+    assert np.array_equal(bits_from_dev(B_out)[:8], B) and not bits_from_dev(B_out)[8:].any()
+    assert L.lora_pool_unit_layout(pool, 1, 0, 0, 0)["rank"] == 8

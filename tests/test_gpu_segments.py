@@ -1,0 +1,125 @@
+"""lora_build_segments against the oracle's canonical segments: bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2604_07173_amd as L
+import workloads as W
+from oracle import lora_oracle as O
+from paper_2604_07173_amd.harness import to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def make_pool(n, E):
+    desc = L.PoolDesc(n, 1, E, [(8, 8)], 8)
+    slab = torch.empty(L.lora_pool_bytes(desc), dtype=torch.uint8, device="cuda")
+    return L.lora_register_pool(desc, slab)
+
+
+def run_segments(pool, aid, eid, P=None):
+    P = len(aid) if P is None else P
+    seg = L.Segments(max(P, 1))
+    for t in (seg.perm, seg.seg_start, seg.seg_key, seg.tiles):
+        t.fill_(-7)
+    d_aid = to_dev(aid) if len(aid) else torch.empty(1, dtype=torch.int32, device="cuda")
+    d_eid = None if eid is None else (to_dev(eid) if len(eid) else torch.empty(1, dtype=torch.int32, device="cuda"))
+    L.lora_build_segments(pool, d_aid, d_eid, P, seg)
+    torch.cuda.synchronize()
+    return seg
+
+
+def compare(seg, aid, eid, n, E):
+    o = O.segments(aid, eid, n, E)
+    counts = seg.counts.cpu().numpy()
+    assert counts[0] == o.S and counts[1] == o.P_act and counts[3] == 0
+    assert np.array_equal(seg.perm.cpu().numpy()[:o.P_act], o.perm)
+    assert np.array_equal(seg.seg_start.cpu().numpy()[:o.S + 1], o.seg_start)
+    assert np.array_equal(seg.seg_key.cpu().numpy()[:o.S], o.seg_key)
+    # tiles: each segment cut in order into blocks of at most tile_rows rows
+    tr = seg.c.tile_rows
+    want = []
+    for s in range(o.S):
+        b, e = int(o.seg_start[s]), int(o.seg_start[s + 1])
+        for r0 in range(b, e, tr):
+            want.append((int(o.seg_key[s]), r0, min(tr, e - r0), s))
+    assert counts[2] == len(want)
+    got = seg.tiles.cpu().numpy()[:len(want)]
+    assert np.array_equal(got, np.array(want, dtype=np.int32).reshape(-1, 4))
+    return o
+
+
+CASES = [
+    # seed, P, n_adapters, n_experts, fraction of -1
+    (0, 1, 1, 1, 0.0), (1, 64, 4, 1, 0.0), (2, 65, 4, 1, 0.3), (3, 256, 64, 1, 0.0),
+    (4, 1000, 7, 5, 0.1), (5, 1024, 32, 8, 0.0), (6, 1025, 32, 8, 0.5), (7, 4097, 3, 2, 0.0),
+    (8, 8192, 256, 128, 0.0), (9, 16384, 8, 1, 0.0), (10, 5000, 300, 300, 0.2),
+    (11, 777, 1, 1, 1.0), (12, 16384, 1000, 64, 0.01),
+]
+
+
+@pytest.mark.parametrize("seed,P,n,E,drop", CASES)
+def test_segments_match_oracle(seed, P, n, E, drop):
+    rng = np.random.default_rng(seed)
+    aid = rng.integers(0, n, size=P).astype(np.int32)
+    aid[rng.random(P) < drop] = -1
+    eid = rng.integers(0, E, size=P).astype(np.int32) if E > 1 else None
+    pool = make_pool(n, E)
+    seg = run_segments(pool, aid, eid)
+    compare(seg, aid, eid, n, E)
+    assert int(seg.status.cpu()[0]) == 0
+    # bit-identical on a second run
+    seg2 = run_segments(pool, aid, eid)
+    P_act = int(seg.counts.cpu()[1])
+    assert torch.equal(seg.perm[:P_act], seg2.perm[:P_act])
+
+
+def test_empty_batch_writes_zero_counts():
+    pool = make_pool(4, 1)
+    seg = L.Segments(1)
+    seg.counts.fill_(9)
+    L.lora_build_segments(pool, None, None, 0, seg)
+    torch.cuda.synchronize()
+    assert seg.counts.cpu().tolist() == [0, 0, 0, 0]
+
+
+def test_invalid_ids_raise_status_bits_and_are_dropped():
+    aid = np.array([0, 5, -1, 2, -7, 1, 2], np.int32)
+    eid = np.array([0, 0, 0, 9, 0, 1, -1], np.int32)
+    pool = make_pool(3, 2)
+    seg = run_segments(pool, aid, eid)
+    o = compare(seg, aid, eid, 3, 2)
+    assert o.n_bad == 4
+    assert int(seg.status.cpu()[0]) == 3      # bad adapter | bad expert
+    seg = run_segments(pool, np.array([0, 1], np.int32), np.array([0, 7], np.int32))
+    assert int(seg.status.cpu()[0]) == 2
+    seg = run_segments(pool, np.array([0, 1], np.int32), np.array([0, 1], np.int32))
+    assert int(seg.status.cpu()[0]) == 0
+
+
+def test_workload_id_structures():
+    """The id structure of the five workloads: Zipf adapters, top-k experts, contiguous
+    prefill requests and their shuffled variant."""
+    for name in ("dense_small", "llama8b_decode", "mixtral_moe_decode", "finegrained_moe_decode",
+                 "prefill"):
+        w = W.WORKLOADS[name]
+        tiny = W.scaled(w, projs=(W.Proj("p", 8, 8, "x"),) if w.kind == "dense" else
+                        (W.Proj("gate", 8, 8, "x"), W.Proj("up", 8, 8, "x"), W.Proj("down", 8, 8, "mid")))
+        for seed in (1234, 1):
+            b = W.make_batch(tiny, seed)
+            pool = make_pool(w.n_adapters, w.n_experts)
+            seg = run_segments(pool, b.adapter_id, b.expert_id)
+            compare(seg, b.adapter_id, b.expert_id, w.n_adapters, w.n_experts)
+    w = W.WORKLOADS["prefill"]
+    b = W.make_batch(W.scaled(w, projs=(W.Proj("p", 8, 8, "x"),)), 3)
+    aid = np.random.default_rng(3).permutation(b.adapter_id)
+    pool = make_pool(w.n_adapters, 1)
+    compare(run_segments(pool, aid, None), aid, None, w.n_adapters, 1)
+
+
+def test_too_many_rows_is_a_host_error():
+    pool = make_pool(2, 1)
+    seg = L.Segments(8)
+    with pytest.raises(L.LoraError) as e:
+        L.lora_build_segments(pool, seg.perm, None, L.LORA_MAX_ROWS + 1, seg)
+    assert e.value.status == -8
