@@ -62,6 +62,9 @@ def load_library():
     global _lib
     if _lib is not None:
         return _lib
+    # torch ships its own HIP runtime; import it first so that liblora binds to the same one
+    # that owns the tensors' memory and streams (two runtimes in one process do not mix)
+    import torch  # noqa: F401
     path = lib_path()
     if not os.path.exists(path):
         raise RuntimeError(f"{path} is not built; run `python -m paper_2604_07173_amd.build` "

@@ -9,8 +9,9 @@ import sys
 PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "liblora.so")
-SOURCES = ["api.hip", "pack.hip", "segments.hip", "shrink.hip", "expand.hip"]
-HEADERS = ["lora_internal.h", "lora_layout.h", os.path.join("..", "..", "include", "lora.h")]
+SOURCES = ["api.hip", "pack.hip", "segments.hip", "shrink.hip", "expand.hip",
+           "shrink_decode.hip", "expand_decode.hip"]
+HEADERS = ["lora_internal.h", "lora_layout.h", "lora_device.h", os.path.join("..", "..", "include", "lora.h")]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -35,7 +36,7 @@ def is_stale() -> bool:
     return any(os.path.getmtime(d) > t for d in deps)
 
 
-def build(verbose: bool = False, jobs: int = 5) -> str:
+def build(verbose: bool = False, jobs: int = 7) -> str:
     """Compile every translation unit and link the shared library. Always compiles."""
     cc = hipcc()
     objdir = os.path.join(PKG_DIR, "_build")

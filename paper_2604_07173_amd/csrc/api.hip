@@ -143,10 +143,20 @@ int check_unit(const lora_pool *p, int adapter, int layer, int expert, int proj)
 }
 
 // upper bound on the number of row tiles a batch of P rows can produce
-int64_t tiles_upper_bound(const lora_pool *p, int P)
+int64_t tiles_upper_bound(const lora_pool *p, int P, int tile_rows)
 {
     const int64_t keys = (int64_t)p->d.n_adapters * p->d.n_experts;
-    return std::min<int64_t>(P, std::min<int64_t>(keys, P) + P / kTileRows);
+    return std::min<int64_t>(P, std::min<int64_t>(keys, P) + P / tile_rows);
+}
+
+// Rows per tile for a batch: decode batches (few rows per adapter/expert cell) get the
+// 16-row tiles of the decode kernels, batches with long segments the 32-row tiles.
+int pick_tile_rows(const lora_pool *p, int P)
+{
+    static const int forced = env_int("LORA_TILE_ROWS", 0, 0, 32);
+    if (forced == kTileRows || forced == kDecodeTileRows) return forced;
+    const int64_t keys = (int64_t)p->d.n_adapters * p->d.n_experts;
+    return (int64_t)P >= 64 * keys ? kTileRows : kDecodeTileRows;
 }
 
 struct KSplit {
@@ -159,7 +169,18 @@ struct KSplit {
 KSplit ksplit_of(const lora_pool *p, int proj, int P)
 {
     const int kblocks = kblocks_of(p->d.proj[proj].h_in);
-    const int64_t tub = std::max<int64_t>(1, tiles_upper_bound(p, P));
+    if (pick_tile_rows(p, P) == kDecodeTileRows) {
+        // decode: parts of about kb_target K-blocks, at most max_parts of them
+        static const int kb_target = env_int("LORA_DEC_KB_PER_PART", 32, 4, 4096);
+        static const int max_parts = env_int("LORA_DEC_MAX_PARTS", 8, 1, kMaxParts);
+        int n = std::min(std::max(1, (kblocks + kb_target - 1) / kb_target), max_parts);
+        int per = ((kblocks + n - 1) / n + 3) / 4 * 4;
+        KSplit k;
+        k.kb_per_part = per;
+        k.n_parts = (kblocks + per - 1) / per;
+        return k;
+    }
+    const int64_t tub = std::max<int64_t>(1, tiles_upper_bound(p, P, kTileRows));
     static const int target = env_int("LORA_SHRINK_ITEMS", 1024, 1, 1 << 20);
     int want = (int)std::min<int64_t>((target + tub - 1) / tub, kMaxParts);
     int by_size = (kblocks + kPartKBlocks - 1) / kPartKBlocks;
@@ -177,7 +198,8 @@ KSplit ksplit_of(const lora_pool *p, int proj, int P)
 int check_segments(const lora_segments *s)
 {
     if (!s) return LORA_ERR_INVALID_ARG;
-    if (s->P < 0 || s->tile_rows != kTileRows) return LORA_ERR_NOT_REGISTERED;
+    if (s->P < 0 || (s->tile_rows != kTileRows && s->tile_rows != kDecodeTileRows))
+        return LORA_ERR_NOT_REGISTERED;
     if (s->P > 0 && (!s->perm || !s->seg_start || !s->seg_key || !s->tiles || !s->counts || !s->status))
         return LORA_ERR_INVALID_ARG;
     return LORA_OK;
@@ -207,8 +229,16 @@ int do_shrink(const lora_pool *pool, int layer, int proj0, int n_fused, const vo
     sp.n_parts = ks.n_parts;
     sp.kb_per_part = ks.kb_per_part;
     sp.rank = pool->d.rank;
+    static const int nt = env_int("LORA_NONTEMPORAL", 1, 0, 1);
+    sp.nontemporal = nt;
+    const int64_t items = tiles_upper_bound(pool, seg->P, seg->tile_rows) * ks.n_parts;
+    if (seg->tile_rows == kDecodeTileRows) {
+        static const int per_cu = env_int("LORA_DEC_SHRINK_WGS_PER_CU", 8, 1, 64);
+        sp.grid = (int)std::min<int64_t>(items, (int64_t)cu_count() * per_cu);
+        LORA_HIP(launch_shrink_decode(sp, st));
+        return LORA_OK;
+    }
     static const int per_cu = env_int("LORA_SHRINK_WGS_PER_CU", 4, 1, 64);
-    const int64_t items = tiles_upper_bound(pool, seg->P) * ks.n_parts;
     sp.grid = (int)std::min<int64_t>(items, (int64_t)cu_count() * per_cu);
     LORA_HIP(launch_shrink(sp, st));
     return LORA_OK;
@@ -245,13 +275,27 @@ int do_expand(const lora_pool *pool, int layer, int proj0, int n_fused, const fl
         else if (ep.n_chunks % 2 == 0) ep.waves = 2;
         else if (ep.n_chunks < 4) ep.waves = ep.n_chunks;
     }
+    ep.out_f32 = out_dtype == LORA_DTYPE_F32;
+    ep.rank = pool->d.rank;
+    static const int nt = env_int("LORA_NONTEMPORAL", 1, 0, 1);
+    ep.nontemporal = nt;
+    const int64_t tub = std::max<int64_t>(1, tiles_upper_bound(pool, seg->P, seg->tile_rows));
+    if (seg->tile_rows == kDecodeTileRows) {
+        // every wave works alone: slices of about chunks_per_item chunks per (tile, projection)
+        static const int cpi = env_int("LORA_DEC_CHUNKS_PER_ITEM", 8, 1, 4096);
+        static const int per_cu = env_int("LORA_DEC_EXPAND_WGS_PER_CU", 3, 1, 64);
+        ep.waves = 4;
+        ep.n_slices = std::max(1, (ep.n_chunks + cpi - 1) / cpi);
+        const int64_t wave_items = tub * n_fused * ep.n_slices;
+        ep.grid = (int)std::min<int64_t>((wave_items + ep.waves - 1) / ep.waves,
+                                         (int64_t)cu_count() * per_cu);
+        LORA_HIP(launch_expand_decode(ep, st));
+        return LORA_OK;
+    }
     const int groups = (ep.n_chunks + ep.waves - 1) / ep.waves;
-    const int64_t tub = std::max<int64_t>(1, tiles_upper_bound(pool, seg->P));
     static const int target = env_int("LORA_EXPAND_ITEMS", 2048, 1, 1 << 20);
     int64_t slices = (target + tub * n_fused - 1) / (tub * n_fused);
     ep.n_slices = (int)std::max<int64_t>(1, std::min<int64_t>(slices, groups));
-    ep.out_f32 = out_dtype == LORA_DTYPE_F32;
-    ep.rank = pool->d.rank;
     static const int per_cu = env_int("LORA_EXPAND_WGS_PER_CU", 4, 1, 64);
     const int64_t items = tub * n_fused * ep.n_slices;
     ep.grid = (int)std::min<int64_t>(items, (int64_t)cu_count() * per_cu);
@@ -525,7 +569,7 @@ int lora_build_segments(const lora_pool *pool, const int32_t *adapter_id, const 
         if (ws_bytes < lora_segments_ws_bytes(P)) return LORA_ERR_BUFFER_TOO_SMALL;
     }
     seg->P = P;
-    seg->tile_rows = kTileRows;
+    seg->tile_rows = pick_tile_rows(pool, P);
     SegParams sp;
     memset(&sp, 0, sizeof sp);
     sp.adapter_id = adapter_id;
@@ -533,7 +577,7 @@ int lora_build_segments(const lora_pool *pool, const int32_t *adapter_id, const 
     sp.P = P;
     sp.n_adapters = pool->d.n_adapters;
     sp.n_experts = pool->d.n_experts;
-    sp.tile_rows = kTileRows;
+    sp.tile_rows = seg->tile_rows;
     const uint32_t n_keys = (uint32_t)pool->d.n_adapters * (uint32_t)pool->d.n_experts;
     int bits = 0;
     while ((n_keys >> bits) != 0) ++bits;      // the sentinel key n_keys must be representable

@@ -12,27 +12,12 @@
 // packed B leaves each lane with eight consecutive output columns of a row, so the y access
 // is one 16-byte load and one 16-byte store per lane with 16 lanes covering 256 contiguous
 // bytes of a row.  B is read exactly once per (tile, chunk).
+#include "lora_device.h"
 #include "lora_internal.h"
 
 namespace lora {
 
 namespace {
-
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) float f32x4;
-typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
-typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
-
-__device__ inline bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
-
-// fp32 -> bf16 bits, round to nearest even (NaN stays NaN)
-__device__ inline unsigned bf16_rne_bits(float f)
-{
-    unsigned u = __float_as_uint(f);
-    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (u >> 16) | 0x40u;
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return u >> 16;
-}
 
 template <int R, bool F32>
 __global__ __launch_bounds__(256) void expand_kernel(ExpandParams p)
@@ -72,18 +57,19 @@ __global__ __launch_bounds__(256) void expand_kernel(ExpandParams p)
             if (row < t.n_rows) {
                 const float *src = vsrc + ((int64_t)(t.row0 + row)) * R + j;
                 for (int part = 0; part < p.n_parts; ++part)
-                    s += *reinterpret_cast<const f32x4 *>(src + (int64_t)part * p.P * R);
+                    s += ld16f(src + (int64_t)part * p.P * R);
                 s *= unit.scale;
             }
-            unsigned hi[4], lo[4];
+            unsigned hi[4];
+            float rem[4];
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const unsigned u = __float_as_uint(s[q]) & 0xFFFF0000u;
                 hi[q] = u >> 16;
-                lo[q] = bf16_rne_bits(s[q] - __uint_as_float(u));
+                rem[q] = s[q] - __uint_as_float(u);
             }
             *reinterpret_cast<u32x2 *>(&v_hi[row][j]) = u32x2{hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16)};
-            *reinterpret_cast<u32x2 *>(&v_lo[row][j]) = u32x2{lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16)};
+            *reinterpret_cast<u32x2 *>(&v_lo[row][j]) = u32x2{pack_bf16_rne(rem[0], rem[1]), pack_bf16_rne(rem[2], rem[3])};
         }
         __syncthreads();
 
@@ -114,7 +100,7 @@ __global__ __launch_bounds__(256) void expand_kernel(ExpandParams p)
                     if (R >= 32) off = (((((int64_t)chunk * 8 + blk) * KS + ks) * 4 + g) * 16 + i16) * 8;
                     else if (R == 16) off = ((((int64_t)chunk * 8 + blk) * 2 + (g & 1)) * 16 + i16) * 8;
                     else off = (((int64_t)chunk * 8 + blk) * 16 + i16) * 8;
-                    b[blk][ks] = *reinterpret_cast<const u32x4 *>(Bp + off);
+                    b[blk][ks] = ld16<false>(Bp + off);
                 }
 
 #pragma unroll
@@ -127,11 +113,11 @@ __global__ __launch_bounds__(256) void expand_kernel(ExpandParams p)
                     const bool ok = col_ok && drow[sub][i] >= 0;
                     if (F32) {
                         const float *yp = static_cast<const float *>(p.y[pj]) + (int64_t)drow[sub][i] * p.ldy + col;
-                        yv[i][0] = ok ? *reinterpret_cast<const u32x4 *>(yp) : zero4;
-                        yv[i][F32 ? 1 : 0] = ok ? *reinterpret_cast<const u32x4 *>(yp + 4) : zero4;
+                        yv[i][0] = ok ? ld16<false>(yp) : zero4;
+                        yv[i][F32 ? 1 : 0] = ok ? ld16<false>(yp + 4) : zero4;
                     } else {
                         const uint16_t *yp = static_cast<const uint16_t *>(p.y[pj]) + (int64_t)drow[sub][i] * p.ldy + col;
-                        yv[i][0] = ok ? *reinterpret_cast<const u32x4 *>(yp) : zero4;
+                        yv[i][0] = ok ? ld16<false>(yp) : zero4;
                     }
                 }
 
@@ -182,8 +168,8 @@ __global__ __launch_bounds__(256) void expand_kernel(ExpandParams p)
                             o0[q] = __uint_as_float(yv[i][0][q]) + acc[q][i];
                             o1[q] = __uint_as_float(yv[i][F32 ? 1 : 0][q]) + acc[4 + q][i];
                         }
-                        *reinterpret_cast<f32x4 *>(yp) = o0;
-                        *reinterpret_cast<f32x4 *>(yp + 4) = o1;
+                        st16<false>(yp, __builtin_bit_cast(u32x4, o0));
+                        st16<false>(yp + 4, __builtin_bit_cast(u32x4, o1));
                     } else {
                         uint16_t *yp = static_cast<uint16_t *>(p.y[pj]) + (int64_t)drow[sub][i] * p.ldy + col;
                         u32x4 o;
@@ -192,9 +178,9 @@ __global__ __launch_bounds__(256) void expand_kernel(ExpandParams p)
                             const unsigned u = yv[i][0][q];
                             const float f0 = __uint_as_float(u << 16) + acc[2 * q][i];
                             const float f1 = __uint_as_float(u & 0xFFFF0000u) + acc[2 * q + 1][i];
-                            o[q] = bf16_rne_bits(f0) | (bf16_rne_bits(f1) << 16);
+                            o[q] = pack_bf16_rne(f0, f1);
                         }
-                        *reinterpret_cast<u32x4 *>(yp) = o;
+                        st16<false>(yp, o);
                     }
                 }
             }

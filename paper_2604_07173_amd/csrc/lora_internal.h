@@ -20,7 +20,8 @@ struct Unit {
 };
 static_assert(sizeof(Unit) == 32, "table entry is 32 bytes");
 
-constexpr int kTileRows = 32;        // rows per tile handed to the kernels
+constexpr int kTileRows = 32;        // rows per tile of the general kernels
+constexpr int kDecodeTileRows = 16;  // rows per tile of the decode kernels
 constexpr int kKBlock = 32;          // K elements per MFMA step (v_mfma_f32_16x16x32_bf16)
 constexpr int kColChunk = 128;       // output columns one wave owns in expand
 constexpr int kPartKBlocks = 32;     // K-blocks one shrink workgroup reduces (1024 inputs)
@@ -79,6 +80,7 @@ struct ShrinkParams {
     int kb_per_part;
     int rank;
     int grid;
+    int nontemporal;         // stream the weights with nontemporal loads
 };
 
 struct ExpandParams {
@@ -101,6 +103,7 @@ struct ExpandParams {
     int out_f32;
     int rank;
     int grid;
+    int nontemporal;         // stream B and y with nontemporal accesses
 };
 
 hipError_t launch_pack_A(const PackParams &p, hipStream_t s);
@@ -110,5 +113,7 @@ hipError_t launch_unpack_B(const PackParams &p, hipStream_t s);
 hipError_t launch_segments(const SegParams &p, hipStream_t s);
 hipError_t launch_shrink(const ShrinkParams &p, hipStream_t s);
 hipError_t launch_expand(const ExpandParams &p, hipStream_t s);
+hipError_t launch_shrink_decode(const ShrinkParams &p, hipStream_t s);   // tiles of <= 16 rows
+hipError_t launch_expand_decode(const ExpandParams &p, hipStream_t s);
 
 }  // namespace lora

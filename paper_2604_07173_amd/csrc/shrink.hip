@@ -11,17 +11,12 @@
 //
 // With two fused projections (the MoE gate and up matrices) the gathered x operand is
 // loaded once and used for both.
+#include "lora_device.h"
 #include "lora_internal.h"
 
 namespace lora {
 
 namespace {
-
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) float f32x4;
-typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
-
-__device__ inline bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
 template <int R, int NPROJ>
 __global__ __launch_bounds__(256) void shrink_kernel(ShrinkParams p)
@@ -91,11 +86,11 @@ __global__ __launch_bounds__(256) void shrink_kernel(ShrinkParams p)
                         w[pj][u][nb] = zero4;
                         if (R >= 16) {
                             if (k_ok)
-                                w[pj][u][nb] = *reinterpret_cast<const u32x4 *>(
+                                w[pj][u][nb] = ld16<false>(
                                     Ap[pj] + (((int64_t)kb * NB + nb) * 64 + lane) * 8);
                         } else {
                             if (k_ok && i16 < 8)
-                                w[pj][u][nb] = *reinterpret_cast<const u32x4 *>(
+                                w[pj][u][nb] = ld16<false>(
                                     Ap[pj] + ((int64_t)kb * 32 + g * 8 + i16) * 8);
                         }
                     }
@@ -104,7 +99,7 @@ __global__ __launch_bounds__(256) void shrink_kernel(ShrinkParams p)
                 for (int sub = 0; sub < SUB; ++sub) {
                     xv[sub][u] = zero4;
                     if (c_ok && rv[sub])
-                        xv[sub][u] = *reinterpret_cast<const u32x4 *>(xp[sub] + kb * kKBlock);
+                        xv[sub][u] = ld16<false>(xp[sub] + kb * kKBlock);
                 }
             }
 #pragma unroll
@@ -147,7 +142,7 @@ __global__ __launch_bounds__(256) void shrink_kernel(ShrinkParams p)
                 s += red[2][pj][sub][nb][l];
                 s += red[3][pj][sub][nb][l];
                 float *dst = p.v[pj] + ((int64_t)part * p.P + t.row0 + row) * R + j;
-                *reinterpret_cast<f32x4 *>(dst) = s;
+                st16f(dst, s);
             }
         }
         __syncthreads();
