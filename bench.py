@@ -35,6 +35,12 @@ def parse_args():
     ap.add_argument("--hot", action="store_true", help="reuse one layer (weights warm in cache)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--all", action="store_true", help="also measure the other workloads (extra field)")
+    ap.add_argument("--launch", choices=["graph", "stream"], default="graph",
+                    help="how the timed steps are launched: one HIP graph holding all K steps "
+                         "(as a serving engine captures a decode iteration), or plain stream launches")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy a few times (reference for scaling "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
     return ap.parse_args()
 
 
@@ -126,7 +132,26 @@ def measure(name, args, steps, warmup, with_cpu_baseline):
         step(warmup + it)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / steps
+    stream_ms_per_step = (t1 - t0) * 1e3 / steps
+    ms_per_step = stream_ms_per_step
+    if args.launch == "graph":
+        # the same K steps recorded once into a HIP graph and replayed: no allocation, no
+        # synchronisation and no memset inside, so the library's launches capture as they are
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            for it in range(steps):
+                step(warmup + it)
+        torch.cuda.synchronize()
+        graph.replay()                      # untimed: first replay uploads the graph
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        graph.replay()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        ms_per_step = (t1 - t0) * 1e3 / steps
+        del graph
 
     # ---- per-launch durations with events on the launch stream ---------------------------
     n_ev = min(steps, 100)
@@ -153,7 +178,8 @@ def measure(name, args, steps, warmup, with_cpu_baseline):
 
     total_bytes = acct["total"]
     res = dict(
-        workload=name, ms_per_step=ms_per_step, tokens_per_s=w.tokens / (ms_per_step * 1e-3),
+        workload=name, ms_per_step=ms_per_step, stream_ms_per_step=stream_ms_per_step,
+        tokens_per_s=w.tokens / (ms_per_step * 1e-3),
         pairs_per_s=w.pairs / (ms_per_step * 1e-3),
         step_gbs=total_bytes / (ms_per_step * 1e-3) / 1e9,
         step_frac_of_peak=total_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
@@ -230,6 +256,14 @@ def main():
         print("bench.py needs a GPU", file=sys.stderr)
         return 1
     torch.cuda.set_device(0)
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)          # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
     main_res = measure(args.workload, args, args.steps, args.warmup, not args.no_cpu_baseline)
     out = {
         "metric": "LoRA-delta tokens/s (MoE-LoRA decode layer call) on 1 MI355X",
@@ -241,7 +275,10 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": args.workload, "layers_in_pool": main_res["layers_in_pool"],
                    "weights": "hot (one layer)" if args.hot else "cold (layer rotation)",
+                   "launch": "one HIP graph of all timed steps" if args.launch == "graph"
+                   else "stream launches",
                    "seed": args.seed, "segments": main_res["segments"], "rows": main_res["pairs"]},
+        "stream_launch_ms_per_step": round(main_res["stream_ms_per_step"], 5),
         "hbm_gbs": round(main_res["step_gbs"], 1),
         "hbm_frac_of_peak": round(main_res["step_frac_of_peak"], 4),
         "algorithmic_bytes_per_step": main_res["algorithmic_bytes"],

@@ -11,7 +11,7 @@ CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "liblora.so")
 SOURCES = ["api.hip", "pack.hip", "segments.hip", "shrink.hip", "expand.hip",
            "shrink_decode.hip", "expand_decode.hip"]
-HEADERS = ["lora_internal.h", "lora_layout.h", "lora_device.h", os.path.join("..", "..", "include", "lora.h")]
+HEADERS = ["lora_internal.h", "lora_layout.h", "lora_device.h", "expand_common.h", os.path.join("..", "..", "include", "lora.h")]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

@@ -279,6 +279,8 @@ int do_expand(const lora_pool *pool, int layer, int proj0, int n_fused, const fl
     ep.rank = pool->d.rank;
     static const int nt = env_int("LORA_NONTEMPORAL", 1, 0, 1);
     ep.nontemporal = nt;
+    static const int dbg = env_int("LORA_DEBUG_EXPAND", 0, 0, 7);
+    ep.debug = dbg;
     const int64_t tub = std::max<int64_t>(1, tiles_upper_bound(pool, seg->P, seg->tile_rows));
     if (seg->tile_rows == kDecodeTileRows) {
         // every wave works alone: slices of about chunks_per_item chunks per (tile, projection)

@@ -12,7 +12,9 @@
 // packed B leaves each lane with eight consecutive output columns of a row, so the y access
 // is one 16-byte load and one 16-byte store per lane with 16 lanes covering 256 contiguous
 // bytes of a row.  B is read exactly once per (tile, chunk).
-#include "lora_device.h"
+#include <type_traits>
+
+#include "expand_common.h"
 #include "lora_internal.h"
 
 namespace lora {
@@ -20,9 +22,10 @@ namespace lora {
 namespace {
 
 template <int R, bool F32>
-__global__ __launch_bounds__(256) void expand_kernel(ExpandParams p)
+__global__ __launch_bounds__(256, 2) void expand_kernel(ExpandParams p)
 {
-    constexpr int KS = R >= 32 ? R / 32 : 1;      // MFMA K steps over the rank
+    using Tile = ExpandTile<R>;
+    constexpr int KS = Tile::KS;                  // MFMA K steps over the rank
     constexpr int TR = kTileRows;
     constexpr int SUB = TR / 16;
     constexpr int LD = R + 8;                     // padded LDS row (bf16 elements)
@@ -91,17 +94,8 @@ __global__ __launch_bounds__(256) void expand_kernel(ExpandParams p)
             const bool col_ok = col < p.h_out;
 
             // packed B of the chunk -> operand registers
-            u32x4 b[8][KS];
-#pragma unroll
-            for (int blk = 0; blk < 8; ++blk)
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    int64_t off;
-                    if (R >= 32) off = (((((int64_t)chunk * 8 + blk) * KS + ks) * 4 + g) * 16 + i16) * 8;
-                    else if (R == 16) off = ((((int64_t)chunk * 8 + blk) * 2 + (g & 1)) * 16 + i16) * 8;
-                    else off = (((int64_t)chunk * 8 + blk) * 16 + i16) * 8;
-                    b[blk][ks] = ld16<false>(Bp + off);
-                }
+            typename Tile::B b;
+            Tile::template load_b<false>(Bp, chunk, lane, b);
 
 #pragma unroll
             for (int sub = 0; sub < SUB; ++sub) {
@@ -121,40 +115,20 @@ __global__ __launch_bounds__(256) void expand_kernel(ExpandParams p)
                     }
                 }
 
-                // v operand of the sub-tile: row i16, K group g
+                // v operand of the sub-tile: row i16, this lane group's K values
                 const int row = sub * 16 + i16;
-                u32x4 a_hi[KS], a_lo[KS];
+                typename Tile::A a;
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
-                    if (R >= 32) {
-                        a_hi[ks] = *reinterpret_cast<const u32x4 *>(&v_hi[row][ks * 32 + g * 8]);
-                        a_lo[ks] = *reinterpret_cast<const u32x4 *>(&v_lo[row][ks * 32 + g * 8]);
-                    } else if (R == 16) {
-                        // K = 32 holds hi (groups 0,1) and lo (groups 2,3) of the 16 rank entries
-                        a_hi[ks] = g < 2 ? *reinterpret_cast<const u32x4 *>(&v_hi[row][(g & 1) * 8])
-                                         : *reinterpret_cast<const u32x4 *>(&v_lo[row][(g & 1) * 8]);
-                        a_lo[ks] = zero4;
-                    } else {
-                        // K = 32 holds hi (group 0), lo (group 1), zeros (groups 2,3)
-                        a_hi[ks] = g == 0 ? *reinterpret_cast<const u32x4 *>(&v_hi[row][0])
-                                 : g == 1 ? *reinterpret_cast<const u32x4 *>(&v_lo[row][0]) : zero4;
-                        a_lo[ks] = zero4;
-                    }
+                    const int jb = Tile::jbase(g, ks);
+                    typedef typename Tile::vec vec;
+                    const vec vh = *reinterpret_cast<const vec *>(&v_hi[row][jb]);
+                    const vec vl = *reinterpret_cast<const vec *>(&v_lo[row][jb]);
+                    a.hi[ks] = (R == 8 && g >= 2) ? vl : vh;
+                    a.lo[ks] = vl;
                 }
-
                 f32x4 acc[8];
-#pragma unroll
-                for (int blk = 0; blk < 8; ++blk) {
-                    acc[blk] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                    for (int ks = 0; ks < KS; ++ks) {
-                        acc[blk] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                            as_bf16x8(a_hi[ks]), as_bf16x8(b[blk][ks]), acc[blk], 0, 0, 0);
-                        if (R >= 32)
-                            acc[blk] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                                as_bf16x8(a_lo[ks]), as_bf16x8(b[blk][ks]), acc[blk], 0, 0, 0);
-                    }
-                }
+                Tile::mma(a, b, acc);
 
                 // y += delta: lane owns columns col .. col+7 of rows 4*g + i
 #pragma unroll

@@ -104,6 +104,7 @@ struct ExpandParams {
     int rank;
     int grid;
     int nontemporal;         // stream B and y with nontemporal accesses
+    int debug;               // timing experiments only (results are wrong when set)
 };
 
 hipError_t launch_pack_A(const PackParams &p, hipStream_t s);

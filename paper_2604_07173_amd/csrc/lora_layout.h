@@ -16,8 +16,11 @@
 //   columns are grouped in chunks of 128; inside a chunk the MFMA column slot n = 0..15 of
 //   sub-block blk = 0..7 is output column 8*n + blk, so that after the eight MFMAs of a
 //   chunk a lane owns eight consecutive output columns of a row (one 16-byte access).
-//   K steps of 32: ks = j/32; within a step lane group gl = (j%32)/8, t = j%8; only
-//   G = min(rank, 32)/8 lane groups are stored.
+//   rank >= 32 (v_mfma_f32_16x16x32_bf16): K steps of 32, ks = j/32; within a step lane
+//     group gl = (j%32)/8 holds t = j%8; a sub-block is 64 lanes x 16 bytes per K step.
+//   rank <= 16 (v_mfma_f32_16x16x16_bf16, four K values per lane): lane group gl = j/4
+//     holds t = j%4; a sub-block is rank/4 lane groups x 16 lanes x 8 bytes, so a wave reads
+//     it with one 8-byte load per lane and no two lanes of a rank-16 tile read the same bytes.
 //   Columns are padded with zeros to a multiple of 128.
 #pragma once
 #include <stdint.h>
@@ -36,15 +39,16 @@ LORA_HD int64_t packA_index(int c, int j, int rank)
     return ((((int64_t)kb * NB + nb) * 64) + g * 16 + n) * 8 + t;
 }
 
-LORA_HD int packB_ksteps(int rank) { return rank >= 32 ? rank / 32 : 1; }
-LORA_HD int packB_groups(int rank) { return rank >= 32 ? 4 : rank / 8; }
-
 LORA_HD int64_t packB_index(int j, int d, int rank)
 {
     const int chunk = d >> 7, dd = d & 127, n = dd >> 3, blk = dd & 7;
-    const int KS = packB_ksteps(rank), G = packB_groups(rank);
+    if (rank <= 16) {
+        const int G = rank >> 2, gl = j >> 2, t = j & 3;
+        return (((((int64_t)chunk * 8 + blk) * G + gl) * 16) + n) * 4 + t;
+    }
+    const int KS = rank >> 5;
     const int ks = j >> 5, gl = (j & 31) >> 3, t = j & 7;
-    return ((((((int64_t)chunk * 8 + blk) * KS + ks) * G + gl) * 16) + n) * 8 + t;
+    return ((((((int64_t)chunk * 8 + blk) * KS + ks) * 4 + gl) * 16) + n) * 8 + t;
 }
 
 }  // namespace lora

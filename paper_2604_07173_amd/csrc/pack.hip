@@ -43,15 +43,15 @@ __global__ __launch_bounds__(256) void pack_B_kernel(PackParams p)
     const int d = (int)(gid % ((int64_t)chunks * 128));
     const int j0 = (int)(gid / ((int64_t)chunks * 128)) * 8;
     uint16_t *packed = (DIR == 0 ? p.dst : const_cast<uint16_t *>(p.src)) +
-                       (int64_t)unit * (DIR == 0 ? p.dst_stride : p.src_stride) +
-                       packB_index(j0, d, p.rank);
+                       (int64_t)unit * (DIR == 0 ? p.dst_stride : p.src_stride);
     uint16_t *plain = (DIR == 0 ? const_cast<uint16_t *>(p.src) : p.dst) +
                       (int64_t)unit * (DIR == 0 ? p.src_stride : p.dst_stride);
     for (int t = 0; t < 8; ++t) {
         const int j = j0 + t;
         const bool in = d < p.h && j < p.src_rank;
-        if (DIR == 0) packed[t] = in ? plain[(int64_t)j * p.h + d] : (uint16_t)0;
-        else if (in) plain[(int64_t)j * p.h + d] = packed[t];
+        uint16_t *q = packed + packB_index(j, d, p.rank);
+        if (DIR == 0) *q = in ? plain[(int64_t)j * p.h + d] : (uint16_t)0;
+        else if (in) plain[(int64_t)j * p.h + d] = *q;
     }
 }
 

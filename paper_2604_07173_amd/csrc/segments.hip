@@ -2,6 +2,7 @@
 // then segment boundaries and row tiles.  One workgroup of 1024 threads does the whole job
 // out of LDS (a batch has at most 16384 rows and the result feeds kernels that run right
 // after it, so latency matters, not bandwidth; gfx950 has 160 KiB of LDS per workgroup).
+// Global memory is only read for the ids and only written for the results.
 //
 // LDS holds key[row] for the whole batch and two 16-bit row-index arrays that the radix
 // passes (8 key bits each, least significant first) ping-pong between; the keys never move.
@@ -9,9 +10,15 @@
 // Stability without order-defining atomics: in every pass wave w owns the contiguous
 // positions [w*CH, (w+1)*CH) of the current order; it walks them 64 at a time in order,
 // ranks equal digits inside a group of 64 by lane order (ballot match) and keeps a running
-// per-digit count of its own; an exclusive scan over (digit, wave) in digit-major order
-// turns the counts into start positions.  Equal keys therefore keep their original order
-// and the output is unique, hence bit-identical run to run.
+// per-digit count of its own (LDS adds whose only effect is a sum, so their order does not
+// matter); an exclusive scan over (digit, wave) in digit-major order turns the counts into
+// start positions.  Equal keys therefore keep their original order and the output is
+// unique, hence bit-identical run to run.
+//
+// Boundaries and tiles: thread t owns `items` consecutive sorted positions and keeps the
+// boundary flags of its positions as a bit mask; three block scans (count of boundaries,
+// last boundary before, first boundary after) give every position its segment index, start
+// and end without reading anything back from global memory.
 #include "lora_internal.h"
 
 namespace lora {
@@ -21,8 +28,17 @@ namespace {
 constexpr int kThreads = 1024;
 constexpr int kWaves = kThreads / 64;
 constexpr int kBins = 256;
+constexpr int kMaxItems = LORA_MAX_ROWS / kThreads;   // positions per thread, fits a 32-bit mask
+static_assert(kMaxItems <= 32, "boundary flags are kept in a 32-bit mask");
 
-__device__ inline int block_excl_scan(int v, int *total, volatile int *wave_sums)
+struct ScanLds {
+    int sum[kWaves];
+    int mx[kWaves];
+    int mn[kWaves];
+};
+
+// exclusive prefix sum over the workgroup, plus the total
+__device__ inline int block_excl_sum(int v, int *total, volatile int *wave_sums)
 {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     int inc = v;
@@ -45,6 +61,51 @@ __device__ inline int block_excl_scan(int v, int *total, volatile int *wave_sums
     return base + inc - v;
 }
 
+// three scans with one pair of barriers: exclusive sum of `cnt` (and total), exclusive
+// running max of `last` over earlier threads, exclusive running min of `first` over later
+// threads
+__device__ inline void block_scan3(int cnt, int last, int first, volatile ScanLds *s,
+                                   int *cnt_before, int *cnt_total, int *last_before,
+                                   int *first_after)
+{
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    int isum = cnt, imax = last, imin = first;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int a = __shfl_up(isum, o, 64), b = __shfl_up(imax, o, 64);
+        const int c = __shfl_down(imin, o, 64);
+        if (lane >= o) {
+            isum += a;
+            imax = max(imax, b);
+        }
+        if (lane + o < 64) imin = min(imin, c);
+    }
+    __syncthreads();
+    if (lane == 63) {
+        s->sum[w] = isum;
+        s->mx[w] = imax;
+    }
+    if (lane == 0) s->mn[w] = imin;
+    __syncthreads();
+    int base = 0, tot = 0, mx = -1, mn = 0x7FFFFFFF;
+#pragma unroll
+    for (int k = 0; k < kWaves; ++k) {
+        const int a = s->sum[k], b = s->mx[k], c = s->mn[k];
+        if (k < w) {
+            base += a;
+            mx = max(mx, b);
+        }
+        if (k > w) mn = min(mn, c);
+        tot += a;
+    }
+    // exclusive within the wave: take the neighbour's inclusive value
+    const int pmax = __shfl_up(imax, 1, 64), nmin = __shfl_down(imin, 1, 64);
+    *cnt_before = base + isum - cnt;
+    *cnt_total = tot;
+    *last_before = lane > 0 ? max(mx, pmax) : mx;
+    *first_after = lane < 63 ? min(mn, nmin) : mn;
+}
+
 // lanes of the wave whose digit equals mine (restricted to valid lanes)
 __device__ inline unsigned long long match_digit(unsigned digit, bool valid)
 {
@@ -61,8 +122,9 @@ __device__ inline unsigned long long match_digit(unsigned digit, bool valid)
 __global__ __launch_bounds__(kThreads) void segments_kernel(SegParams p)
 {
     __shared__ unsigned hist[kWaves][kBins];
-    __shared__ int wave_sums[kWaves];
+    __shared__ ScanLds scan;
     __shared__ unsigned status_bits;
+    __shared__ int n_active_total;
     extern __shared__ __attribute__((aligned(16))) unsigned char dyn_lds[];
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -76,33 +138,38 @@ __global__ __launch_bounds__(kThreads) void segments_kernel(SegParams p)
     const int wave_base = w * items * 64;
     const unsigned long long lt_mask = (1ull << lane) - 1ull;
 
-    if (tid == 0) status_bits = 0;
+    if (tid == 0) {
+        status_bits = 0;
+        n_active_total = 0;
+    }
+    for (int b = tid; b < kWaves * kBins; b += kThreads) (&hist[0][0])[b] = 0;
     __syncthreads();
 
-    // ---- key of every row --------------------------------------------------------------
-    int n_active = 0;
-    unsigned bad = 0;
+    // ---- key of every row (independent loads, four in flight per thread) -----------------
+    {
+        int n_active = 0;
+        unsigned bad = 0;
 #pragma unroll 4
-    for (int i = tid; i < P; i += kThreads) {
-        const int a = p.adapter_id[i];
-        const int e = p.expert_id ? p.expert_id[i] : 0;
-        unsigned k = n_keys;
-        if (a != -1) {
+        for (int i = tid; i < P; i += kThreads) {
+            const int a = p.adapter_id[i];
+            const int e = p.expert_id ? p.expert_id[i] : 0;
             const bool a_ok = a >= 0 && a < p.n_adapters;
             const bool e_ok = e >= 0 && e < p.n_experts;
-            if (a_ok && e_ok) {
-                k = (unsigned)a * (unsigned)p.n_experts + (unsigned)e;
-                ++n_active;
-            } else {
+            const bool none = a == -1;
+            const bool ok = a_ok && e_ok;
+            key_of[i] = ok ? (unsigned)a * (unsigned)p.n_experts + (unsigned)e : n_keys;
+            n_active += ok ? 1 : 0;
+            if (!none && !ok)
                 bad |= (a_ok ? 0u : (unsigned)LORA_STATUS_BAD_ADAPTER) |
                        (e_ok ? 0u : (unsigned)LORA_STATUS_BAD_EXPERT);
-            }
         }
-        key_of[i] = k;
+        if (bad) atomicOr(&status_bits, bad);          // OR and + are order-independent
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) n_active += __shfl_xor(n_active, o, 64);
+        if (lane == 0 && n_active) atomicAdd(&n_active_total, n_active);
     }
-    if (bad) atomicOr(&status_bits, bad);   // OR is order-independent
-    int P_act;
-    block_excl_scan(n_active, &P_act, wave_sums);   // its barriers also publish key_of
+    __syncthreads();
+    const int P_act = n_active_total;
 
     // ---- radix passes over the row order ----------------------------------------------
     for (int pass = 0; pass < p.passes; ++pass) {
@@ -110,19 +177,25 @@ __global__ __launch_bounds__(kThreads) void segments_kernel(SegParams p)
         const bool last = pass == p.passes - 1;
         const uint16_t *src = order[(pass + 1) & 1];   // unused in pass 0 (identity order)
         uint16_t *dst = order[pass & 1];
+        unsigned *my_hist = hist[w];
 
-        for (int b = tid; b < kWaves * kBins; b += kThreads) (&hist[0][0])[b] = 0;
-        __syncthreads();
-
-        volatile unsigned *my_hist = hist[w];
-        // count
-        for (int g = 0; g < items; ++g) {
-            const int i = wave_base + g * 64 + lane;
-            const bool valid = i < P;
-            const unsigned row = valid ? (pass == 0 ? (unsigned)i : (unsigned)src[i]) : 0u;
-            const unsigned digit = valid ? (key_of[row] >> shift) & 255u : 0u;
-            const unsigned long long m = match_digit(digit, valid);
-            if (valid && (m & lt_mask) == 0) my_hist[digit] += (unsigned)__popcll(m);
+        // count: digits of four groups are fetched together, then ranked in order
+        for (int g0 = 0; g0 < items; g0 += 4) {
+            unsigned dig[4];
+            bool val[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int i = wave_base + (g0 + u) * 64 + lane;
+                val[u] = (g0 + u < items) && i < P;
+                const unsigned row = val[u] ? (pass == 0 ? (unsigned)i : (unsigned)src[i]) : 0u;
+                dig[u] = val[u] ? (key_of[row] >> shift) & 255u : 0u;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                if (g0 + u >= items) break;
+                const unsigned long long m = match_digit(dig[u], val[u]);
+                if (val[u] && (m & lt_mask) == 0) atomicAdd(&my_hist[dig[u]], (unsigned)__popcll(m));
+            }
         }
         __syncthreads();
 
@@ -133,7 +206,7 @@ __global__ __launch_bounds__(kThreads) void segments_kernel(SegParams p)
             const unsigned c0 = hist[w0][bin], c1 = hist[w0 + 1][bin], c2 = hist[w0 + 2][bin],
                            c3 = hist[w0 + 3][bin];
             int tot;
-            const unsigned base = (unsigned)block_excl_scan((int)(c0 + c1 + c2 + c3), &tot, wave_sums);
+            const unsigned base = (unsigned)block_excl_sum((int)(c0 + c1 + c2 + c3), &tot, scan.sum);
             hist[w0][bin] = base;
             hist[w0 + 1][bin] = base + c0;
             hist[w0 + 2][bin] = base + c0 + c1;
@@ -142,79 +215,92 @@ __global__ __launch_bounds__(kThreads) void segments_kernel(SegParams p)
         __syncthreads();
 
         // scatter
-        for (int g = 0; g < items; ++g) {
-            const int i = wave_base + g * 64 + lane;
-            const bool valid = i < P;
-            const unsigned row = valid ? (pass == 0 ? (unsigned)i : (unsigned)src[i]) : 0u;
-            const unsigned digit = valid ? (key_of[row] >> shift) & 255u : 0u;
-            const unsigned long long m = match_digit(digit, valid);
-            if (valid) {
-                const unsigned pos = my_hist[digit] + (unsigned)__popcll(m & lt_mask);
-                dst[pos] = (uint16_t)row;
-                if (last) p.perm[pos] = (int32_t)row;
+        for (int g0 = 0; g0 < items; g0 += 4) {
+            unsigned dig[4], row[4];
+            bool val[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int i = wave_base + (g0 + u) * 64 + lane;
+                val[u] = (g0 + u < items) && i < P;
+                row[u] = val[u] ? (pass == 0 ? (unsigned)i : (unsigned)src[i]) : 0u;
+                dig[u] = val[u] ? (key_of[row[u]] >> shift) & 255u : 0u;
             }
-            __builtin_amdgcn_wave_barrier();
-            if (valid && (m & lt_mask) == 0) my_hist[digit] += (unsigned)__popcll(m);
-            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                if (g0 + u >= items) break;
+                const unsigned long long m = match_digit(dig[u], val[u]);
+                // every lane reads the digit's running start before the leader advances it;
+                // LDS operations of one wave execute in program order
+                const unsigned first = *(volatile unsigned *)&my_hist[dig[u]];
+                if (val[u]) {
+                    const unsigned pos = first + (unsigned)__popcll(m & lt_mask);
+                    dst[pos] = (uint16_t)row[u];
+                    if (last) p.perm[pos] = (int32_t)row[u];
+                }
+                __builtin_amdgcn_wave_barrier();
+                if (val[u] && (m & lt_mask) == 0) atomicAdd(&my_hist[dig[u]], (unsigned)__popcll(m));
+                __builtin_amdgcn_wave_barrier();
+            }
         }
         __syncthreads();
+        if (!last) {
+            for (int b = tid; b < kWaves * kBins; b += kThreads) (&hist[0][0])[b] = 0;
+            __syncthreads();
+        }
     }
     const uint16_t *sorted = order[(p.passes - 1) & 1];
 
-    // ---- segment boundaries: thread t owns sorted positions t*items .. t*items+items-1 ---
+    // ---- segment boundaries of my positions as a bit mask --------------------------------
     const int i0 = tid * items;
-    int n_flag = 0;
+    unsigned F = 0;
     {
         unsigned prev = (i0 > 0 && i0 - 1 < P_act) ? key_of[sorted[i0 - 1]] : 0xFFFFFFFFu;
         for (int q = 0; q < items; ++q) {
             const int i = i0 + q;
             if (i >= P_act) break;
             const unsigned k = key_of[sorted[i]];
-            n_flag += (i == 0 || k != prev) ? 1 : 0;
+            if (i == 0 || k != prev) F |= 1u << q;
             prev = k;
         }
     }
-    int S;
-    int sidx = block_excl_scan(n_flag, &S, wave_sums);
+    const int my_last = F ? i0 + 31 - __clz(F) : -1;
+    const int my_first = F ? i0 + __ffs(F) - 1 : 0x7FFFFFFF;
+    int seg_before, S, start_before, next_after;
+    block_scan3(__popc(F), my_last, my_first, &scan, &seg_before, &S, &start_before, &next_after);
+    next_after = min(next_after, P_act);
+
+    // ---- segment records and tile starts -------------------------------------------------
+    const int TR = p.tile_rows;       // a power of two
+    unsigned T = 0;                   // tile starts among my positions
     {
-        unsigned prev = (i0 > 0 && i0 - 1 < P_act) ? key_of[sorted[i0 - 1]] : 0xFFFFFFFFu;
+        int sidx = seg_before;
+        int seg_begin = start_before;
         for (int q = 0; q < items; ++q) {
             const int i = i0 + q;
             if (i >= P_act) break;
-            const unsigned k = key_of[sorted[i]];
-            if (i == 0 || k != prev) {
+            if (F & (1u << q)) {
+                seg_begin = i;
                 p.seg_start[sidx] = i;
-                p.seg_key[sidx] = (int32_t)k;
+                p.seg_key[sidx] = (int32_t)key_of[sorted[i]];
                 ++sidx;
             }
-            prev = k;
+            if (((i - seg_begin) & (TR - 1)) == 0) T |= 1u << q;
         }
     }
     if (tid == 0) p.seg_start[S] = P_act;
-    __syncthreads();   // seg_start / seg_key written above are read below by other threads
-
-    // ---- tiles: thread t owns segments t*items .. ; a tile never crosses a segment -------
-    const int TR = p.tile_rows;
-    int n_my_tiles = 0;
-    for (int q = 0; q < items; ++q) {
-        const int s = i0 + q;
-        if (s >= S) break;
-        n_my_tiles += (p.seg_start[s + 1] - p.seg_start[s] + TR - 1) / TR;
-    }
     int n_tiles;
-    int tix = block_excl_scan(n_my_tiles, &n_tiles, wave_sums);
-    for (int q = 0; q < items; ++q) {
-        const int s = i0 + q;
-        if (s >= S) break;
-        const int b = p.seg_start[s], e = p.seg_start[s + 1], k = p.seg_key[s];
-        for (int r0 = b; r0 < e; r0 += TR) {
-            lora_tile t;
-            t.key = k;
-            t.row0 = r0;
-            t.n_rows = min(TR, e - r0);
-            t.seg = s;
-            p.tiles[tix++] = t;
-        }
+    int tix = block_excl_sum(__popc(T), &n_tiles, scan.sum);
+    for (unsigned rest = T; rest; rest &= rest - 1) {
+        const int q = __ffs(rest) - 1;
+        const int i = i0 + q;
+        const unsigned above = q >= 31 ? 0u : F & (0xFFFFFFFEu << q);      // boundaries after i
+        const int seg_end = above ? i0 + __ffs(above) - 1 : next_after;
+        lora_tile t;
+        t.key = (int32_t)key_of[sorted[i]];
+        t.row0 = i;
+        t.n_rows = min(TR, seg_end - i);
+        t.seg = seg_before + __popc(F & (0xFFFFFFFFu >> (31 - q))) - 1;
+        p.tiles[tix++] = t;
     }
     if (tid == 0) {
         p.counts[0] = S;

@@ -19,7 +19,7 @@ namespace lora {
 namespace {
 
 template <int R, int NPROJ>
-__global__ __launch_bounds__(256) void shrink_kernel(ShrinkParams p)
+__global__ __launch_bounds__(256, 2) void shrink_kernel(ShrinkParams p)
 {
     constexpr int NB = R >= 16 ? R / 16 : 1;              // 16-wide blocks of the rank index
     constexpr int KB = R <= 16 ? 8 : (R == 32 ? 4 : 2);   // K blocks loaded per step

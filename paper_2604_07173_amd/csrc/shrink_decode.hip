@@ -65,7 +65,7 @@ struct ShrinkWave {
 };
 
 template <int R, int NPROJ, bool NT>
-__global__ __launch_bounds__(256) void shrink16_kernel(ShrinkParams p)
+__global__ __launch_bounds__(256, 2) void shrink16_kernel(ShrinkParams p)
 {
     using Wave = ShrinkWave<R, NPROJ, NT>;
     constexpr int NB = Wave::NB, KB = Wave::KB;

@@ -62,10 +62,11 @@ def test_packB_is_a_bijection_and_groups_eight_columns_per_lane(exe, r):
     h = 256
     ix = indices(exe, 1, h, r).reshape(r, h)
     assert sorted(ix.ravel().tolist()) == list(range(h * r))
-    for j0 in range(0, r, 8):
+    run_len = 8 if r >= 32 else 4        # K values one lane holds contiguously
+    for j0 in range(0, r, run_len):
         for d in range(h):
-            run = ix[j0:j0 + 8, d]
-            assert run[0] % 8 == 0 and np.array_equal(run, run[0] + np.arange(8))
+            run = ix[j0:j0 + run_len, d]
+            assert run[0] % run_len == 0 and np.array_equal(run, run[0] + np.arange(run_len))
     # a 128-column chunk occupies one contiguous span of 128*r values
     assert ix[:, :128].min() == 0 and ix[:, :128].max() == 128 * r - 1
     # columns 8n .. 8n+7 belong to MFMA column slot n of sub-blocks 0..7
