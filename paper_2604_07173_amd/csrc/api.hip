@@ -285,7 +285,7 @@ int do_expand(const lora_pool *pool, int layer, int proj0, int n_fused, const fl
     if (seg->tile_rows == kDecodeTileRows) {
         // every wave works alone: slices of about chunks_per_item chunks per (tile, projection)
         static const int cpi = env_int("LORA_DEC_CHUNKS_PER_ITEM", 8, 1, 4096);
-        static const int per_cu = env_int("LORA_DEC_EXPAND_WGS_PER_CU", 3, 1, 64);
+        static const int per_cu = env_int("LORA_DEC_EXPAND_WGS_PER_CU", 4, 1, 64);
         ep.waves = 4;
         ep.n_slices = std::max(1, (ep.n_chunks + cpi - 1) / cpi);
         const int64_t wave_items = tub * n_fused * ep.n_slices;
@@ -584,6 +584,8 @@ int lora_build_segments(const lora_pool *pool, const int32_t *adapter_id, const 
     int bits = 0;
     while ((n_keys >> bits) != 0) ++bits;      // the sentinel key n_keys must be representable
     sp.passes = std::max(1, (bits + 7) / 8);
+    static const int seg_stop = env_int("LORA_SEG_STOP", 0, 0, 16);
+    sp.stop = seg_stop;
     sp.perm = seg->perm;
     sp.seg_start = seg->seg_start;
     sp.seg_key = seg->seg_key;

@@ -54,6 +54,7 @@ struct SegParams {
     int n_experts;
     int tile_rows;
     int passes;              // radix passes of 8 bits over the key
+    int stop;                // timing experiments only
     int32_t *perm;
     int32_t *seg_start;
     int32_t *seg_key;

@@ -38,11 +38,11 @@ struct ScanLds {
 };
 
 // exclusive prefix sum over the workgroup, plus the total
-__device__ inline int block_excl_sum(int v, int *total, volatile int *wave_sums)
+__device__ __noinline__ int block_excl_sum(int v, int *total, volatile int *wave_sums)
 {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     int inc = v;
-#pragma unroll
+#pragma unroll 1
     for (int o = 1; o < 64; o <<= 1) {
         int t = __shfl_up(inc, o, 64);
         if (lane >= o) inc += t;
@@ -50,13 +50,16 @@ __device__ inline int block_excl_sum(int v, int *total, volatile int *wave_sums)
     __syncthreads();
     if (lane == 63) wave_sums[w] = inc;
     __syncthreads();
-    int base = 0, tot = 0;
-#pragma unroll
-    for (int k = 0; k < kWaves; ++k) {
-        int s = wave_sums[k];
-        if (k < w) base += s;
-        tot += s;
+    // wave totals: lane k < 16 fetches total k, a wave reduction does the rest
+    const int mine = lane < kWaves ? wave_sums[lane] : 0;
+    int tot = mine, base = lane < w ? mine : 0;
+#pragma unroll 1
+    for (int o = 8; o > 0; o >>= 1) {
+        tot += __shfl_xor(tot, o, 64);
+        base += __shfl_xor(base, o, 64);
     }
+    tot = __shfl(tot, 0, 64);
+    base = __shfl(base, 0, 64);
     *total = tot;
     return base + inc - v;
 }
@@ -64,13 +67,13 @@ __device__ inline int block_excl_sum(int v, int *total, volatile int *wave_sums)
 // three scans with one pair of barriers: exclusive sum of `cnt` (and total), exclusive
 // running max of `last` over earlier threads, exclusive running min of `first` over later
 // threads
-__device__ inline void block_scan3(int cnt, int last, int first, volatile ScanLds *s,
+__device__ inline void block_scan3(int cnt, int last, int first, ScanLds *s,
                                    int *cnt_before, int *cnt_total, int *last_before,
                                    int *first_after)
 {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     int isum = cnt, imax = last, imin = first;
-#pragma unroll
+#pragma unroll 1
     for (int o = 1; o < 64; o <<= 1) {
         const int a = __shfl_up(isum, o, 64), b = __shfl_up(imax, o, 64);
         const int c = __shfl_down(imin, o, 64);
@@ -87,17 +90,21 @@ __device__ inline void block_scan3(int cnt, int last, int first, volatile ScanLd
     }
     if (lane == 0) s->mn[w] = imin;
     __syncthreads();
-    int base = 0, tot = 0, mx = -1, mn = 0x7FFFFFFF;
-#pragma unroll
-    for (int k = 0; k < kWaves; ++k) {
-        const int a = s->sum[k], b = s->mx[k], c = s->mn[k];
-        if (k < w) {
-            base += a;
-            mx = max(mx, b);
-        }
-        if (k > w) mn = min(mn, c);
-        tot += a;
+    // lane k < 16 fetches wave k's values; a 16-lane butterfly combines them
+    const bool in = lane < kWaves;
+    const int a = in ? s->sum[lane] : 0, b = in ? s->mx[lane] : -1, c = in ? s->mn[lane] : 0x7FFFFFFF;
+    int tot = a, base = lane < w ? a : 0, mx = lane < w ? b : -1, mn = lane > w ? c : 0x7FFFFFFF;
+#pragma unroll 1
+    for (int o = 8; o > 0; o >>= 1) {
+        tot += __shfl_xor(tot, o, 64);
+        base += __shfl_xor(base, o, 64);
+        mx = max(mx, __shfl_xor(mx, o, 64));
+        mn = min(mn, __shfl_xor(mn, o, 64));
     }
+    tot = __shfl(tot, 0, 64);
+    base = __shfl(base, 0, 64);
+    mx = __shfl(mx, 0, 64);
+    mn = __shfl(mn, 0, 64);
     // exclusive within the wave: take the neighbour's inclusive value
     const int pmax = __shfl_up(imax, 1, 64), nmin = __shfl_down(imin, 1, 64);
     *cnt_before = base + isum - cnt;
@@ -106,17 +113,31 @@ __device__ inline void block_scan3(int cnt, int last, int first, volatile ScanLd
     *first_after = lane < 63 ? min(mn, nmin) : mn;
 }
 
-// lanes of the wave whose digit equals mine (restricted to valid lanes)
-__device__ inline unsigned long long match_digit(unsigned digit, bool valid)
+// Lanes of the wave whose digit equals mine (restricted to valid lanes), as two 32-bit
+// halves.  Per key bit: one ballot, then keep the lanes whose bit equals mine.
+struct Match {
+    unsigned lo, hi;
+};
+
+__device__ __noinline__ Match match_digit(unsigned digit, bool valid)
 {
-    unsigned long long m = __ballot(valid);
-#pragma unroll
+    const unsigned long long v = __ballot(valid);
+    Match m = {(unsigned)v, (unsigned)(v >> 32)};
+#pragma unroll 1
     for (int b = 0; b < 8; ++b) {
-        const bool bit = (digit >> b) & 1u;
+        const unsigned bit = (digit >> b) & 1u;
         const unsigned long long bal = __ballot(valid && bit);
-        m &= bit ? bal : ~bal;
+        const unsigned same = 0u - bit;                  // all ones if my bit is set
+        m.lo &= ~((unsigned)bal ^ same);                 // bit ? bal : ~bal
+        m.hi &= ~((unsigned)(bal >> 32) ^ same);
     }
     return m;
+}
+
+// number of lanes below mine in the mask
+__device__ inline unsigned lanes_below(Match m)
+{
+    return __builtin_amdgcn_mbcnt_hi(m.hi, __builtin_amdgcn_mbcnt_lo(m.lo, 0u));
 }
 
 __global__ __launch_bounds__(kThreads) void segments_kernel(SegParams p)
@@ -136,7 +157,8 @@ __global__ __launch_bounds__(kThreads) void segments_kernel(SegParams p)
     const unsigned n_keys = (unsigned)p.n_adapters * (unsigned)p.n_experts;      // sentinel key
     const int items = (P + kThreads - 1) / kThreads;       // 64-row groups per wave
     const int wave_base = w * items * 64;
-    const unsigned long long lt_mask = (1ull << lane) - 1ull;
+    const bool park = n_keys < 0xFFFFu;                    // room for a 16-bit rank above the key
+    const unsigned key_mask = park ? 0xFFFFu : 0xFFFFFFFFu;
 
     if (tid == 0) {
         status_bits = 0;
@@ -149,7 +171,7 @@ __global__ __launch_bounds__(kThreads) void segments_kernel(SegParams p)
     {
         int n_active = 0;
         unsigned bad = 0;
-#pragma unroll 4
+#pragma unroll 1
         for (int i = tid; i < P; i += kThreads) {
             const int a = p.adapter_id[i];
             const int e = p.expert_id ? p.expert_id[i] : 0;
@@ -164,12 +186,13 @@ __global__ __launch_bounds__(kThreads) void segments_kernel(SegParams p)
                        (e_ok ? 0u : (unsigned)LORA_STATUS_BAD_EXPERT);
         }
         if (bad) atomicOr(&status_bits, bad);          // OR and + are order-independent
-#pragma unroll
+#pragma unroll 1
         for (int o = 32; o > 0; o >>= 1) n_active += __shfl_xor(n_active, o, 64);
         if (lane == 0 && n_active) atomicAdd(&n_active_total, n_active);
     }
     __syncthreads();
     const int P_act = n_active_total;
+    if (p.stop == 1) return;
 
     // ---- radix passes over the row order ----------------------------------------------
     for (int pass = 0; pass < p.passes; ++pass) {
@@ -179,26 +202,28 @@ __global__ __launch_bounds__(kThreads) void segments_kernel(SegParams p)
         uint16_t *dst = order[pass & 1];
         unsigned *my_hist = hist[w];
 
-        // count: digits of four groups are fetched together, then ranked in order
-        for (int g0 = 0; g0 < items; g0 += 4) {
-            unsigned dig[4];
-            bool val[4];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int i = wave_base + (g0 + u) * 64 + lane;
-                val[u] = (g0 + u < items) && i < P;
-                const unsigned row = val[u] ? (pass == 0 ? (unsigned)i : (unsigned)src[i]) : 0u;
-                dig[u] = val[u] ? (key_of[row] >> shift) & 255u : 0u;
-            }
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                if (g0 + u >= items) break;
-                const unsigned long long m = match_digit(dig[u], val[u]);
-                if (val[u] && (m & lt_mask) == 0) atomicAdd(&my_hist[dig[u]], (unsigned)__popcll(m));
-            }
+        // count: rank of every element among the equal digits of its wave; when keys fit
+        // 16 bits the rank is parked in the upper half of the key word for the scatter
+#pragma unroll 1
+        for (int g = 0; g < items; ++g) {
+            const int i = wave_base + g * 64 + lane;
+            const bool val = i < P;
+            const unsigned row = val ? (pass == 0 ? (unsigned)i : (unsigned)src[i]) : 0u;
+            const unsigned k = val ? key_of[row] & key_mask : 0u;
+            const unsigned dig = (k >> shift) & 255u;
+            const Match m = match_digit(dig, val);
+            const unsigned below = lanes_below(m);
+            // every lane reads the digit's running count before the leader advances it; LDS
+            // operations of one wave execute in program order
+            const unsigned first = *(volatile unsigned *)&my_hist[dig];
+            if (val && park) key_of[row] = k | ((first + below) << 16);
+            __builtin_amdgcn_wave_barrier();
+            if (val && below == 0) my_hist[dig] = first + __popc(m.lo) + __popc(m.hi);
+            __builtin_amdgcn_wave_barrier();
         }
         __syncthreads();
 
+        if (p.stop == 2) return;
         // exclusive scan over (digit, wave), digit-major: thread t owns digit t/4 and waves
         // 4*(t%4) .. 4*(t%4)+3
         {
@@ -214,32 +239,30 @@ __global__ __launch_bounds__(kThreads) void segments_kernel(SegParams p)
         }
         __syncthreads();
 
-        // scatter
-        for (int g0 = 0; g0 < items; g0 += 4) {
-            unsigned dig[4], row[4];
-            bool val[4];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int i = wave_base + (g0 + u) * 64 + lane;
-                val[u] = (g0 + u < items) && i < P;
-                row[u] = val[u] ? (pass == 0 ? (unsigned)i : (unsigned)src[i]) : 0u;
-                dig[u] = val[u] ? (key_of[row[u]] >> shift) & 255u : 0u;
+        if (p.stop == 3) return;
+        // scatter: position = start of (digit, wave) + rank within it
+#pragma unroll 1
+        for (int g = 0; g < items; ++g) {
+            const int i = wave_base + g * 64 + lane;
+            const bool val = i < P;
+            const unsigned row = val ? (pass == 0 ? (unsigned)i : (unsigned)src[i]) : 0u;
+            const unsigned kw = val ? key_of[row] : 0u;
+            const unsigned dig = ((kw & key_mask) >> shift) & 255u;
+            unsigned pos;
+            if (park) {
+                pos = my_hist[dig] + (kw >> 16);
+            } else {
+                const Match m = match_digit(dig, val);
+                const unsigned below = lanes_below(m);
+                const unsigned first = *(volatile unsigned *)&my_hist[dig];
+                pos = first + below;
+                __builtin_amdgcn_wave_barrier();
+                if (val && below == 0) my_hist[dig] = first + __popc(m.lo) + __popc(m.hi);
+                __builtin_amdgcn_wave_barrier();
             }
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                if (g0 + u >= items) break;
-                const unsigned long long m = match_digit(dig[u], val[u]);
-                // every lane reads the digit's running start before the leader advances it;
-                // LDS operations of one wave execute in program order
-                const unsigned first = *(volatile unsigned *)&my_hist[dig[u]];
-                if (val[u]) {
-                    const unsigned pos = first + (unsigned)__popcll(m & lt_mask);
-                    dst[pos] = (uint16_t)row[u];
-                    if (last) p.perm[pos] = (int32_t)row[u];
-                }
-                __builtin_amdgcn_wave_barrier();
-                if (val[u] && (m & lt_mask) == 0) atomicAdd(&my_hist[dig[u]], (unsigned)__popcll(m));
-                __builtin_amdgcn_wave_barrier();
+            if (val) {
+                dst[pos] = (uint16_t)row;
+                if (last) p.perm[pos] = (int32_t)row;
             }
         }
         __syncthreads();
@@ -249,16 +272,17 @@ __global__ __launch_bounds__(kThreads) void segments_kernel(SegParams p)
         }
     }
     const uint16_t *sorted = order[(p.passes - 1) & 1];
+    if (p.stop == 4) return;
 
     // ---- segment boundaries of my positions as a bit mask --------------------------------
     const int i0 = tid * items;
     unsigned F = 0;
     {
-        unsigned prev = (i0 > 0 && i0 - 1 < P_act) ? key_of[sorted[i0 - 1]] : 0xFFFFFFFFu;
+        unsigned prev = (i0 > 0 && i0 - 1 < P_act) ? (key_of[sorted[i0 - 1]] & key_mask) : 0xFFFFFFFFu;
         for (int q = 0; q < items; ++q) {
             const int i = i0 + q;
             if (i >= P_act) break;
-            const unsigned k = key_of[sorted[i]];
+            const unsigned k = key_of[sorted[i]] & key_mask;
             if (i == 0 || k != prev) F |= 1u << q;
             prev = k;
         }
@@ -268,6 +292,7 @@ __global__ __launch_bounds__(kThreads) void segments_kernel(SegParams p)
     int seg_before, S, start_before, next_after;
     block_scan3(__popc(F), my_last, my_first, &scan, &seg_before, &S, &start_before, &next_after);
     next_after = min(next_after, P_act);
+    if (p.stop == 5) return;
 
     // ---- segment records and tile starts -------------------------------------------------
     const int TR = p.tile_rows;       // a power of two
@@ -281,13 +306,14 @@ __global__ __launch_bounds__(kThreads) void segments_kernel(SegParams p)
             if (F & (1u << q)) {
                 seg_begin = i;
                 p.seg_start[sidx] = i;
-                p.seg_key[sidx] = (int32_t)key_of[sorted[i]];
+                p.seg_key[sidx] = (int32_t)(key_of[sorted[i]] & key_mask);
                 ++sidx;
             }
             if (((i - seg_begin) & (TR - 1)) == 0) T |= 1u << q;
         }
     }
     if (tid == 0) p.seg_start[S] = P_act;
+    if (p.stop == 6) return;
     int n_tiles;
     int tix = block_excl_sum(__popc(T), &n_tiles, scan.sum);
     for (unsigned rest = T; rest; rest &= rest - 1) {
@@ -296,7 +322,7 @@ __global__ __launch_bounds__(kThreads) void segments_kernel(SegParams p)
         const unsigned above = q >= 31 ? 0u : F & (0xFFFFFFFEu << q);      // boundaries after i
         const int seg_end = above ? i0 + __ffs(above) - 1 : next_after;
         lora_tile t;
-        t.key = (int32_t)key_of[sorted[i]];
+        t.key = (int32_t)(key_of[sorted[i]] & key_mask);
         t.row0 = i;
         t.n_rows = min(TR, seg_end - i);
         t.seg = seg_before + __popc(F & (0xFFFFFFFFu >> (31 - q))) - 1;
