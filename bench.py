@@ -154,21 +154,23 @@ def measure(name, args, steps, warmup, with_cpu_baseline):
         del graph
 
     # ---- per-launch durations with events on the launch stream ---------------------------
-    n_ev = min(steps, 100)
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(len(phases) + 1)] for _ in range(n_ev)]
-    for it in range(n_ev):
-        layer = it % n_layers
-        evs[it][0].record()
-        for k, ph in enumerate(phases):
-            ph.fn(layer)
-            evs[it][k + 1].record()
-    torch.cuda.synchronize()
+    # Each launch of the step is repeated back to back between two events (layers rotating,
+    # so weights stay cold), which is how a kernel trace sees it; recording an event after
+    # every single launch would add the event's own cost to each of them.
+    reps = max(8, min(steps, 40))
     per_phase = {}
     for k, ph in enumerate(phases):
-        ts = np.array([evs[it][k].elapsed_time(evs[it][k + 1]) for it in range(n_ev)]) * 1e3  # us
-        per_phase[ph.name] = dict(us=float(np.mean(ts)), us_median=float(np.median(ts)),
-                                  bytes=int(ph.bytes),
-                                  gbs=float(ph.bytes / (np.mean(ts) * 1e-6) / 1e9))
+        step(0)                                   # valid segments / intermediates for this phase
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for r in range(reps):
+            ph.fn(r % n_layers)
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / reps
+        per_phase[ph.name] = dict(us=float(us), bytes=int(ph.bytes),
+                                  gbs=float(ph.bytes / (us * 1e-6) / 1e9))
     dom = max(phases[1:], key=lambda ph: per_phase[ph.name]["us"])
     d = per_phase[dom.name]
     roofline = dict(bound="hbm", kernel=dom.name, achieved=round(d["gbs"], 1), peak=HBM_PEAK_GBS,
