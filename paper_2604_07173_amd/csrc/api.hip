@@ -279,8 +279,6 @@ int do_expand(const lora_pool *pool, int layer, int proj0, int n_fused, const fl
     ep.rank = pool->d.rank;
     static const int nt = env_int("LORA_NONTEMPORAL", 1, 0, 1);
     ep.nontemporal = nt;
-    static const int dbg = env_int("LORA_DEBUG_EXPAND", 0, 0, 7);
-    ep.debug = dbg;
     const int64_t tub = std::max<int64_t>(1, tiles_upper_bound(pool, seg->P, seg->tile_rows));
     if (seg->tile_rows == kDecodeTileRows) {
         // every wave works alone: slices of about chunks_per_item chunks per (tile, projection)
@@ -584,8 +582,6 @@ int lora_build_segments(const lora_pool *pool, const int32_t *adapter_id, const 
     int bits = 0;
     while ((n_keys >> bits) != 0) ++bits;      // the sentinel key n_keys must be representable
     sp.passes = std::max(1, (bits + 7) / 8);
-    static const int seg_stop = env_int("LORA_SEG_STOP", 0, 0, 16);
-    sp.stop = seg_stop;
     sp.perm = seg->perm;
     sp.seg_start = seg->seg_start;
     sp.seg_key = seg->seg_key;

@@ -115,8 +115,8 @@ struct ExpandWave {
 };
 
 template <int R, bool F32, int NI>
-__device__ inline void expand_item(const ExpandParams &p, const lora_tile &t, int pj, int c0, int c1,
-                                   int lane)
+__device__ inline void expand_item(const ExpandParams &p, const lora_tile &t, const Unit &unit, int pj,
+                                   int c0, int c1, int lane)
 {
     using Tile = ExpandTile<R>;
     constexpr int KS = Tile::KS, KV = Tile::KV, ESZ = F32 ? 4 : 2;
@@ -125,14 +125,13 @@ __device__ inline void expand_item(const ExpandParams &p, const lora_tile &t, in
     w.g = lane >> 4;
     w.i16 = lane & 15;
     w.h_out = p.h_out;
-    const Unit *unit = p.units + ((int64_t)t.key * p.n_proj + p.proj0 + pj);
-    w.Bp = (p.debug & 4) ? p.units[p.proj0 + pj].B : unit->B;
-    const float scale = unit->scale;
+    w.Bp = unit.B;
+    const float scale = unit.scale;
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
         const int r = 4 * i + w.g;                       // row of result register i
-        w.rok[i] = r < t.n_rows && !(p.debug & 1);
-        const int dst = (p.debug & 2) ? 0 : p.perm[t.row0 + min(r, t.n_rows - 1)];
+        w.rok[i] = r < t.n_rows;
+        const int dst = p.perm[t.row0 + min(r, t.n_rows - 1)];
         w.yrow[i] = static_cast<char *>(p.y[pj]) + (int64_t)dst * p.ldy * ESZ;
     }
 
@@ -164,13 +163,19 @@ __device__ inline void expand_item(const ExpandParams &p, const lora_tile &t, in
     w.run(c0, c1);
 }
 
+// tiles, units and counts are passed again as restrict-qualified kernel arguments: with a
+// wave-uniform index the compiler then reads them through the scalar cache, which shortens
+// the dependent chain tile -> unit -> first data load.
 template <int R, bool F32>
-__global__ __launch_bounds__(256, 2) void expand16_kernel(ExpandParams p)
+__global__ __launch_bounds__(256, 2) void expand16_kernel(ExpandParams p,
+                                                          const lora_tile *__restrict__ tiles,
+                                                          const Unit *__restrict__ units,
+                                                          const int32_t *__restrict__ counts)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wpb = blockDim.x >> 6;
-    const int gw = blockIdx.x * wpb + wave, nw = gridDim.x * wpb;
-    const int n_tiles = p.counts[2];
+    const int gw = __builtin_amdgcn_readfirstlane(blockIdx.x * wpb + wave), nw = gridDim.x * wpb;
+    const int n_tiles = counts[2];
     const int per_tile = p.n_fused * p.n_slices;
     const int n_items = n_tiles * per_tile;
     const int cps = (p.n_chunks + p.n_slices - 1) / p.n_slices;   // chunks per slice
@@ -182,12 +187,13 @@ __global__ __launch_bounds__(256, 2) void expand16_kernel(ExpandParams p)
         const int slice = rem - pj * p.n_slices;
         const int c0 = slice * cps, c1 = min(c0 + cps, p.n_chunks);
         if (c0 >= c1) continue;
-        const lora_tile t = p.tiles[tile_ix];
+        const lora_tile t = tiles[tile_ix];
+        const Unit unit = units[(int64_t)t.key * p.n_proj + p.proj0 + pj];
         switch ((t.n_rows + 3) >> 2) {              // wave-uniform
-        case 1: expand_item<R, F32, 1>(p, t, pj, c0, c1, lane); break;
-        case 2: expand_item<R, F32, 2>(p, t, pj, c0, c1, lane); break;
-        case 3: expand_item<R, F32, 3>(p, t, pj, c0, c1, lane); break;
-        default: expand_item<R, F32, 4>(p, t, pj, c0, c1, lane); break;
+        case 1: expand_item<R, F32, 1>(p, t, unit, pj, c0, c1, lane); break;
+        case 2: expand_item<R, F32, 2>(p, t, unit, pj, c0, c1, lane); break;
+        case 3: expand_item<R, F32, 3>(p, t, unit, pj, c0, c1, lane); break;
+        default: expand_item<R, F32, 4>(p, t, unit, pj, c0, c1, lane); break;
         }
     }
 }
@@ -197,9 +203,9 @@ hipError_t launch_r(const ExpandParams &p, hipStream_t s)
 {
     const dim3 block(p.waves * 64);
     if (p.out_f32)
-        hipLaunchKernelGGL((expand16_kernel<R, true>), dim3(p.grid), block, 0, s, p);
+        hipLaunchKernelGGL((expand16_kernel<R, true>), dim3(p.grid), block, 0, s, p, p.tiles, p.units, p.counts);
     else
-        hipLaunchKernelGGL((expand16_kernel<R, false>), dim3(p.grid), block, 0, s, p);
+        hipLaunchKernelGGL((expand16_kernel<R, false>), dim3(p.grid), block, 0, s, p, p.tiles, p.units, p.counts);
     return hipGetLastError();
 }
 

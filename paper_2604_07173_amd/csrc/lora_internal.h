@@ -54,7 +54,6 @@ struct SegParams {
     int n_experts;
     int tile_rows;
     int passes;              // radix passes of 8 bits over the key
-    int stop;                // timing experiments only
     int32_t *perm;
     int32_t *seg_start;
     int32_t *seg_key;
@@ -105,7 +104,6 @@ struct ExpandParams {
     int rank;
     int grid;
     int nontemporal;         // stream B and y with nontemporal accesses
-    int debug;               // timing experiments only (results are wrong when set)
 };
 
 hipError_t launch_pack_A(const PackParams &p, hipStream_t s);

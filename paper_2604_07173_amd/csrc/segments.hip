@@ -192,7 +192,6 @@ __global__ __launch_bounds__(kThreads) void segments_kernel(SegParams p)
     }
     __syncthreads();
     const int P_act = n_active_total;
-    if (p.stop == 1) return;
 
     // ---- radix passes over the row order ----------------------------------------------
     for (int pass = 0; pass < p.passes; ++pass) {
@@ -222,8 +221,6 @@ __global__ __launch_bounds__(kThreads) void segments_kernel(SegParams p)
             __builtin_amdgcn_wave_barrier();
         }
         __syncthreads();
-
-        if (p.stop == 2) return;
         // exclusive scan over (digit, wave), digit-major: thread t owns digit t/4 and waves
         // 4*(t%4) .. 4*(t%4)+3
         {
@@ -238,8 +235,6 @@ __global__ __launch_bounds__(kThreads) void segments_kernel(SegParams p)
             hist[w0 + 3][bin] = base + c0 + c1 + c2;
         }
         __syncthreads();
-
-        if (p.stop == 3) return;
         // scatter: position = start of (digit, wave) + rank within it
 #pragma unroll 1
         for (int g = 0; g < items; ++g) {
@@ -272,7 +267,6 @@ __global__ __launch_bounds__(kThreads) void segments_kernel(SegParams p)
         }
     }
     const uint16_t *sorted = order[(p.passes - 1) & 1];
-    if (p.stop == 4) return;
 
     // ---- segment boundaries of my positions as a bit mask --------------------------------
     const int i0 = tid * items;
@@ -292,7 +286,6 @@ __global__ __launch_bounds__(kThreads) void segments_kernel(SegParams p)
     int seg_before, S, start_before, next_after;
     block_scan3(__popc(F), my_last, my_first, &scan, &seg_before, &S, &start_before, &next_after);
     next_after = min(next_after, P_act);
-    if (p.stop == 5) return;
 
     // ---- segment records and tile starts -------------------------------------------------
     const int TR = p.tile_rows;       // a power of two
@@ -313,7 +306,6 @@ __global__ __launch_bounds__(kThreads) void segments_kernel(SegParams p)
         }
     }
     if (tid == 0) p.seg_start[S] = P_act;
-    if (p.stop == 6) return;
     int n_tiles;
     int tix = block_excl_sum(__popc(T), &n_tiles, scan.sum);
     for (unsigned rest = T; rest; rest &= rest - 1) {

@@ -64,8 +64,14 @@ struct ShrinkWave {
     }
 };
 
+// tiles, units and counts are passed again as restrict-qualified kernel arguments: with a
+// workgroup-uniform index the compiler then reads them through the scalar cache, which
+// shortens the dependent chain tile -> unit -> first data load.
 template <int R, int NPROJ, bool NT>
-__global__ __launch_bounds__(256, 2) void shrink16_kernel(ShrinkParams p)
+__global__ __launch_bounds__(256, 2) void shrink16_kernel(ShrinkParams p,
+                                                          const lora_tile *__restrict__ tiles,
+                                                          const Unit *__restrict__ units,
+                                                          const int32_t *__restrict__ counts)
 {
     using Wave = ShrinkWave<R, NPROJ, NT>;
     constexpr int NB = Wave::NB, KB = Wave::KB;
@@ -77,7 +83,7 @@ __global__ __launch_bounds__(256, 2) void shrink16_kernel(ShrinkParams p)
     w.g = w.lane >> 4;
     w.i16 = w.lane & 15;
     w.h_in = p.h_in;
-    const int n_tiles = p.counts[2];
+    const int n_tiles = counts[2];
     const int n_items = n_tiles * p.n_parts;
     const int kblocks = (p.h_in + kKBlock - 1) / kKBlock;
     const int kb_per_wave = (p.kb_per_part + 3) >> 2;
@@ -85,10 +91,10 @@ __global__ __launch_bounds__(256, 2) void shrink16_kernel(ShrinkParams p)
     for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
         const int tile_ix = item / p.n_parts;
         const int part = item - tile_ix * p.n_parts;
-        const lora_tile t = p.tiles[tile_ix];
+        const lora_tile t = tiles[tile_ix];
 #pragma unroll
         for (int pj = 0; pj < NPROJ; ++pj)
-            w.Ap[pj] = p.units[(int64_t)t.key * p.n_proj + p.proj0 + pj].A;
+            w.Ap[pj] = units[(int64_t)t.key * p.n_proj + p.proj0 + pj].A;
         w.row_ok = w.i16 < t.n_rows;
         {
             int s = p.perm[t.row0 + min(w.i16, t.n_rows - 1)];
@@ -147,9 +153,9 @@ template <int R, int NPROJ>
 hipError_t launch_rn(const ShrinkParams &p, hipStream_t s)
 {
     if (p.nontemporal)
-        hipLaunchKernelGGL((shrink16_kernel<R, NPROJ, true>), dim3(p.grid), dim3(256), 0, s, p);
+        hipLaunchKernelGGL((shrink16_kernel<R, NPROJ, true>), dim3(p.grid), dim3(256), 0, s, p, p.tiles, p.units, p.counts);
     else
-        hipLaunchKernelGGL((shrink16_kernel<R, NPROJ, false>), dim3(p.grid), dim3(256), 0, s, p);
+        hipLaunchKernelGGL((shrink16_kernel<R, NPROJ, false>), dim3(p.grid), dim3(256), 0, s, p, p.tiles, p.units, p.counts);
     return hipGetLastError();
 }
 
