@@ -170,10 +170,15 @@ KSplit ksplit_of(const lora_pool *p, int proj, int P)
 {
     const int kblocks = kblocks_of(p->d.proj[proj].h_in);
     if (pick_tile_rows(p, P) == kDecodeTileRows) {
-        // decode: parts of about kb_target K-blocks, at most max_parts of them
+        // decode: parts of about kb_target K-blocks, more of them when the batch has so few
+        // tiles that the chip would not be filled otherwise, at most max_parts
         static const int kb_target = env_int("LORA_DEC_KB_PER_PART", 32, 4, 4096);
         static const int max_parts = env_int("LORA_DEC_MAX_PARTS", 8, 1, kMaxParts);
-        int n = std::min(std::max(1, (kblocks + kb_target - 1) / kb_target), max_parts);
+        static const int want_wgs = env_int("LORA_DEC_SHRINK_ITEMS", 1024, 1, 1 << 20);
+        const int64_t tub = std::max<int64_t>(1, tiles_upper_bound(p, P, kDecodeTileRows));
+        int n = std::max(1, (kblocks + kb_target - 1) / kb_target);
+        n = std::max<int>(n, (int)std::min<int64_t>((want_wgs + tub - 1) / tub, kblocks / 4));
+        n = std::min(std::max(n, 1), max_parts);
         int per = ((kblocks + n - 1) / n + 3) / 4 * 4;
         KSplit k;
         k.kb_per_part = per;
@@ -282,8 +287,13 @@ int do_expand(const lora_pool *pool, int layer, int proj0, int n_fused, const fl
     const int64_t tub = std::max<int64_t>(1, tiles_upper_bound(pool, seg->P, seg->tile_rows));
     if (seg->tile_rows == kDecodeTileRows) {
         // every wave works alone: slices of about chunks_per_item chunks per (tile, projection)
-        static const int cpi = env_int("LORA_DEC_CHUNKS_PER_ITEM", 8, 1, 4096);
+        // chunks per wave item: long enough to amortise the per-item prologue, short enough
+        // that a small batch still yields a few thousand wave items
+        static const int cpi_max = env_int("LORA_DEC_CHUNKS_PER_ITEM", 8, 1, 4096);
+        static const int want_items = env_int("LORA_DEC_EXPAND_ITEMS", 4096, 1, 1 << 22);
         static const int per_cu = env_int("LORA_DEC_EXPAND_WGS_PER_CU", 4, 1, 64);
+        const int64_t units = tub * n_fused * ep.n_chunks;
+        const int cpi = (int)std::max<int64_t>(1, std::min<int64_t>(cpi_max, units / want_items));
         ep.waves = 4;
         ep.n_slices = std::max(1, (ep.n_chunks + cpi - 1) / cpi);
         const int64_t wave_items = tub * n_fused * ep.n_slices;
