@@ -153,6 +153,7 @@ int64_t tiles_upper_bound(const lora_pool *p, int P, int tile_rows)
 // 16-row tiles of the decode kernels, batches with long segments the 32-row tiles.
 int pick_tile_rows(const lora_pool *p, int P)
 {
+    if (p->d.rank == 8) return kDecodeTileRows;      // the 32-row shrink has no rank-8 form
     static const int forced = env_int("LORA_TILE_ROWS", 0, 0, 32);
     if (forced == kTileRows || forced == kDecodeTileRows) return forced;
     const int64_t keys = (int64_t)p->d.n_adapters * p->d.n_experts;
@@ -161,6 +162,7 @@ int pick_tile_rows(const lora_pool *p, int P)
 
 struct KSplit {
     int n_parts, kb_per_part;
+    bool wave_per_tile;
 };
 
 // How the K range of a shrink is cut into parts: enough work items to fill the chip when the
@@ -168,7 +170,7 @@ struct KSplit {
 // pool and P, so lora_shrink, lora_expand and lora_v_bytes agree.
 KSplit ksplit_of(const lora_pool *p, int proj, int P)
 {
-    const int kblocks = kblocks_of(p->d.proj[proj].h_in);
+    const int kblocks = kblocks_of(p->d.proj[proj].h_in, p->d.rank);
     if (pick_tile_rows(p, P) == kDecodeTileRows) {
         // decode: parts of about kb_target K-blocks, more of them when the batch has so few
         // tiles that the chip would not be filled otherwise, at most max_parts
@@ -176,6 +178,17 @@ KSplit ksplit_of(const lora_pool *p, int proj, int P)
         static const int max_parts = env_int("LORA_DEC_MAX_PARTS", 8, 1, kMaxParts);
         static const int want_wgs = env_int("LORA_DEC_SHRINK_ITEMS", 1024, 1, 1 << 20);
         const int64_t tub = std::max<int64_t>(1, tiles_upper_bound(p, P, kDecodeTileRows));
+        // thousands of tiles over a short K range: one wave per tile, K not split at all
+        static const int wpt = env_int("LORA_DEC_WAVE_PER_TILE", -1, -1, 1);
+        static const int wpt_tiles = env_int("LORA_DEC_WAVE_PER_TILE_MIN_TILES", 4096, 1, 1 << 20);
+        static const int wpt_k = env_int("LORA_DEC_WAVE_PER_TILE_MAX_K", 4096, 32, 1 << 20);
+        if (wpt == 1 || (wpt < 0 && tub >= wpt_tiles && p->d.proj[proj].h_in <= wpt_k)) {
+            KSplit k;
+            k.kb_per_part = kblocks;
+            k.n_parts = 1;
+            k.wave_per_tile = true;
+            return k;
+        }
         int n = std::max(1, (kblocks + kb_target - 1) / kb_target);
         n = std::max<int>(n, (int)std::min<int64_t>((want_wgs + tub - 1) / tub, kblocks / 4));
         n = std::min(std::max(n, 1), max_parts);
@@ -183,6 +196,7 @@ KSplit ksplit_of(const lora_pool *p, int proj, int P)
         KSplit k;
         k.kb_per_part = per;
         k.n_parts = (kblocks + per - 1) / per;
+        k.wave_per_tile = false;
         return k;
     }
     const int64_t tub = std::max<int64_t>(1, tiles_upper_bound(p, P, kTileRows));
@@ -197,6 +211,7 @@ KSplit ksplit_of(const lora_pool *p, int proj, int P)
     KSplit k;
     k.kb_per_part = per;
     k.n_parts = (kblocks + per - 1) / per;
+    k.wave_per_tile = false;
     return k;
 }
 
@@ -239,7 +254,9 @@ int do_shrink(const lora_pool *pool, int layer, int proj0, int n_fused, const vo
     const int64_t items = tiles_upper_bound(pool, seg->P, seg->tile_rows) * ks.n_parts;
     if (seg->tile_rows == kDecodeTileRows) {
         static const int per_cu = env_int("LORA_DEC_SHRINK_WGS_PER_CU", 8, 1, 64);
-        sp.grid = (int)std::min<int64_t>(items, (int64_t)cu_count() * per_cu);
+        sp.wave_per_tile = ks.wave_per_tile;
+        const int64_t wgs = ks.wave_per_tile ? (items + 3) / 4 : items;
+        sp.grid = (int)std::min<int64_t>(wgs, (int64_t)cu_count() * per_cu);
         LORA_HIP(launch_shrink_decode(sp, st));
         return LORA_OK;
     }
@@ -302,12 +319,15 @@ int do_expand(const lora_pool *pool, int layer, int proj0, int n_fused, const fl
         LORA_HIP(launch_expand_decode(ep, st));
         return LORA_OK;
     }
-    const int groups = (ep.n_chunks + ep.waves - 1) / ep.waves;
-    static const int target = env_int("LORA_EXPAND_ITEMS", 2048, 1, 1 << 20);
-    int64_t slices = (target + tub * n_fused - 1) / (tub * n_fused);
-    ep.n_slices = (int)std::max<int64_t>(1, std::min<int64_t>(slices, groups));
-    static const int per_cu = env_int("LORA_EXPAND_WGS_PER_CU", 4, 1, 64);
-    const int64_t items = tub * n_fused * ep.n_slices;
+    // general kernel: a workgroup walks over tile_group consecutive tiles with one chunk per
+    // wave held in registers; the group is as long as still leaves enough workgroups
+    const int cgroups = (ep.n_chunks + ep.waves - 1) / ep.waves;
+    static const int target = env_int("LORA_EXPAND_ITEMS", 1536, 1, 1 << 20);
+    static const int tg_max = env_int("LORA_EXPAND_TILE_GROUP", 1, 1, 1024);
+    ep.tile_group = (int)std::max<int64_t>(1, std::min<int64_t>(tg_max, tub * n_fused * cgroups / target));
+    ep.n_slices = 1;
+    static const int per_cu = env_int("LORA_EXPAND_WGS_PER_CU", 8, 1, 64);
+    const int64_t items = ((tub + ep.tile_group - 1) / ep.tile_group) * n_fused * cgroups;
     ep.grid = (int)std::min<int64_t>(items, (int64_t)cu_count() * per_cu);
     LORA_HIP(launch_expand(ep, st));
     return LORA_OK;

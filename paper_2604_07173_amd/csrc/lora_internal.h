@@ -28,9 +28,10 @@ constexpr int kPartKBlocks = 32;     // K-blocks one shrink workgroup reduces (1
 constexpr int kMaxParts = 64;
 
 // ---- packed layout sizes ---------------------------------------------------------------
-inline int kblocks_of(int h_in) { return (h_in + kKBlock - 1) / kKBlock; }
+inline int kunit_of(int rank) { return rank == 8 ? 64 : kKBlock; }   // K values per packed A block
+inline int kblocks_of(int h_in, int rank) { return (h_in + kunit_of(rank) - 1) / kunit_of(rank); }
 inline int chunks_of(int h_out) { return (h_out + kColChunk - 1) / kColChunk; }
-inline size_t packed_A_bytes(int h_in, int rank) { return (size_t)kblocks_of(h_in) * kKBlock * rank * 2; }
+inline size_t packed_A_bytes(int h_in, int rank) { return (size_t)kblocks_of(h_in, rank) * kunit_of(rank) * rank * 2; }
 inline size_t packed_B_bytes(int h_out, int rank) { return (size_t)chunks_of(h_out) * kColChunk * rank * 2; }
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
@@ -81,6 +82,7 @@ struct ShrinkParams {
     int rank;
     int grid;
     int nontemporal;         // stream the weights with nontemporal loads
+    int wave_per_tile;       // decode kernel: every wave takes a whole tile (no K split across waves)
 };
 
 struct ExpandParams {
@@ -98,7 +100,8 @@ struct ExpandParams {
     int64_t ldy;
     int h_out;
     int n_chunks;            // 128-column chunks
-    int n_slices;            // workgroups per (tile, projection)
+    int n_slices;            // decode kernel: wave items per (tile, projection)
+    int tile_group;          // general kernel: consecutive tiles one workgroup walks over
     int waves;               // waves per workgroup
     int out_f32;
     int rank;

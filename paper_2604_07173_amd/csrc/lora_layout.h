@@ -9,8 +9,11 @@
 // Shrink operand, A[h_in][rank] (K = input index c, M = rank index j):
 //   rank >= 16: block (kb = c/32, nb = j/16) of 64 lanes x 8 values;
 //               lane 16*g + (j%16) holds c = 32*kb + 8*g + t, t = 0..7.
-//   rank == 8 : block kb of 32 lanes x 8 values; lane 8*g + j holds c = 32*kb + 8*g + t.
-//   K is padded with zeros to a multiple of 32.
+//   rank == 8 : block q of 64 lanes x 8 values covers 64 K values: lane 16*g + 8*half + j
+//               holds c = 64*q + 32*half + 8*g + t, so that no lane of the 1 KiB block is
+//               idle; the kernel multiplies the block twice, once with the x values of each
+//               half, and keeps rows 0..7 of the first product and rows 8..15 of the second.
+//   K is padded with zeros to a multiple of 32 (rank 8: 64).
 //
 // Expand operand, B[rank][h_out] (K = rank index j, N = output column d):
 //   columns are grouped in chunks of 128; inside a chunk the MFMA column slot n = 0..15 of
@@ -31,10 +34,17 @@
 
 namespace lora {
 
+// K values per packed block of the shrink operand
+LORA_HD int packA_kunit(int rank) { return rank == 8 ? 64 : 32; }
+
 LORA_HD int64_t packA_index(int c, int j, int rank)
 {
-    const int kb = c >> 5, g = (c & 31) >> 3, t = c & 7;
-    if (rank == 8) return (((int64_t)kb * 32) + g * 8 + j) * 8 + t;
+    const int g = (c & 31) >> 3, t = c & 7;
+    if (rank == 8) {
+        const int q = c >> 6, half = (c >> 5) & 1;
+        return (((int64_t)q * 64) + g * 16 + half * 8 + j) * 8 + t;
+    }
+    const int kb = c >> 5;
     const int NB = rank >> 4, nb = j >> 4, n = j & 15;
     return ((((int64_t)kb * NB + nb) * 64) + g * 16 + n) * 8 + t;
 }

@@ -9,18 +9,17 @@ namespace lora {
 template <int DIR>
 __global__ __launch_bounds__(256) void pack_A_kernel(PackParams p)
 {
-    const int kblocks = (p.h + 31) / 32;
-    const int64_t groups = (int64_t)kblocks * 4 * p.rank;     // (kb, g, j)
+    const int kunit = packA_kunit(p.rank);
+    const int k_pad = (p.h + kunit - 1) / kunit * kunit;
+    const int64_t groups = (int64_t)(k_pad / 8) * p.rank;       // (c / 8, j)
     const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (gid >= groups) return;
     const int unit = blockIdx.y;
     const int j = (int)(gid % p.rank);
-    const int g = (int)((gid / p.rank) & 3);
-    const int kb = (int)(gid / ((int64_t)p.rank * 4));
-    const int c0 = kb * 32 + g * 8;
+    const int c0 = (int)(gid / p.rank) * 8;
     uint16_t *packed = (DIR == 0 ? p.dst : const_cast<uint16_t *>(p.src)) +
                        (int64_t)unit * (DIR == 0 ? p.dst_stride : p.src_stride) +
-                       packA_index(c0, j, p.rank);
+                       packA_index(c0, j, p.rank);               // t = 0..7 are contiguous
     uint16_t *plain = (DIR == 0 ? const_cast<uint16_t *>(p.src) : p.dst) +
                       (int64_t)unit * (DIR == 0 ? p.src_stride : p.dst_stride);
     for (int t = 0; t < 8; ++t) {
@@ -66,11 +65,11 @@ static hipError_t launch_pack(K kernel, const PackParams &p, int64_t groups, hip
 
 hipError_t launch_pack_A(const PackParams &p, hipStream_t s)
 {
-    return launch_pack(pack_A_kernel<0>, p, (int64_t)kblocks_of(p.h) * 4 * p.rank, s);
+    return launch_pack(pack_A_kernel<0>, p, (int64_t)kblocks_of(p.h, p.rank) * (kunit_of(p.rank) / 8) * p.rank, s);
 }
 hipError_t launch_unpack_A(const PackParams &p, hipStream_t s)
 {
-    return launch_pack(pack_A_kernel<1>, p, (int64_t)kblocks_of(p.h) * 4 * p.rank, s);
+    return launch_pack(pack_A_kernel<1>, p, (int64_t)kblocks_of(p.h, p.rank) * (kunit_of(p.rank) / 8) * p.rank, s);
 }
 hipError_t launch_pack_B(const PackParams &p, hipStream_t s)
 {

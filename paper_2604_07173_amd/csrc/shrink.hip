@@ -9,6 +9,8 @@
 // in a fixed order and stored as this part's slice of v; lora_expand adds the parts, again
 // in a fixed order, so results are bit-identical run to run.
 //
+// Ranks 16, 32 and 64; rank-8 pools always use the 16-row-tile kernels.
+//
 // With two fused projections (the MoE gate and up matrices) the gathered x operand is
 // loaded once and used for both.
 #include "lora_device.h"
@@ -21,8 +23,8 @@ namespace {
 template <int R, int NPROJ>
 __global__ __launch_bounds__(256, 2) void shrink_kernel(ShrinkParams p)
 {
-    constexpr int NB = R >= 16 ? R / 16 : 1;              // 16-wide blocks of the rank index
-    constexpr int KB = R <= 16 ? 8 : (R == 32 ? 4 : 2);   // K blocks loaded per step
+    constexpr int NB = R / 16;                            // 16-wide blocks of the rank index
+    constexpr int KB = R == 16 ? 8 : (R == 32 ? 4 : 2);   // K blocks loaded per step
     constexpr int SUB = kTileRows / 16;                   // 16-row sub-tiles per tile
     __shared__ f32x4 red[4][NPROJ][SUB][NB][64];
 
@@ -84,15 +86,9 @@ __global__ __launch_bounds__(256, 2) void shrink_kernel(ShrinkParams p)
 #pragma unroll
                     for (int nb = 0; nb < NB; ++nb) {
                         w[pj][u][nb] = zero4;
-                        if (R >= 16) {
-                            if (k_ok)
-                                w[pj][u][nb] = ld16<false>(
-                                    Ap[pj] + (((int64_t)kb * NB + nb) * 64 + lane) * 8);
-                        } else {
-                            if (k_ok && i16 < 8)
-                                w[pj][u][nb] = ld16<false>(
-                                    Ap[pj] + ((int64_t)kb * 32 + g * 8 + i16) * 8);
-                        }
+                        if (k_ok)
+                            w[pj][u][nb] = ld16<false>(
+                                Ap[pj] + (((int64_t)kb * NB + nb) * 64 + lane) * 8);
                     }
                 const bool c_ok = k_ok && (kb * kKBlock + g * 8 < p.h_in);
 #pragma unroll
@@ -165,8 +161,7 @@ hipError_t launch_shrink(const ShrinkParams &p, hipStream_t s)
 {
     if (p.grid <= 0) return hipSuccess;
     switch (p.rank) {
-    case 8: return launch_r<8>(p, s);
-    case 16: return launch_r<16>(p, s);
+    case 16: return launch_r<16>(p, s);       // rank 8 always runs with 16-row tiles
     case 32: return launch_r<32>(p, s);
     case 64: return launch_r<64>(p, s);
     default: return hipErrorInvalidValue;

@@ -1,13 +1,21 @@
 // Shrink for decode batches (tiles of at most 16 rows): v = gather(x) * A.
 //
-// Work item = (row tile, K part); a workgroup of four waves takes one item and each wave
-// owns a quarter of the part's K range.  A wave streams its slice of the packed A (and of
-// the second fused projection's A) with 16-byte loads that are contiguous per wave, two
-// steps in flight (software pipeline: the loads of step s+1 are issued before the MFMAs of
-// step s), and multiplies it with the tile's gathered x rows.  The rank index sits on the M
-// side of v_mfma_f32_16x16x32_bf16 and the rows on the N side, so a lane ends up with four
-// consecutive rank entries of one row.  The four waves' sums are added through LDS in a
-// fixed order and stored as this part's slice of v.
+// Two ways of dealing out the work, chosen on the host:
+//  * K split: work item = (row tile, K part); a workgroup of four waves takes one item, each
+//    wave owns a quarter of the part's K range, and the four waves' sums are added through
+//    LDS in a fixed order.  For batches with few tiles and long inputs.
+//  * wave per tile: every wave takes a whole tile over the whole K range, no LDS, no barrier.
+//    For batches with thousands of small tiles and short inputs (fine-grained MoE).
+// In both a wave streams its slice of the packed A (and of the second fused projection's A)
+// with 16-byte loads that are contiguous per wave, two steps in flight (the loads of step
+// s+1 are issued before the MFMAs of step s; all loads are unconditional so the loop is
+// branch-free and the hardware counters keep them outstanding), and multiplies it with the
+// tile's gathered x rows.  The rank index sits on the M side of v_mfma_f32_16x16x32_bf16 and
+// the rows on the N side, so a lane ends up with four consecutive rank entries of one row.
+//
+// Rank 8: a packed block holds 64 K values (two 32-deep halves side by side in the 16 M
+// rows), is multiplied once with each half's x values, and rows 0..7 of the first product
+// plus rows 8..15 of the second give the eight rank entries.
 #include "lora_device.h"
 #include "lora_internal.h"
 
@@ -17,19 +25,27 @@ namespace {
 
 template <int R, int NPROJ, bool NT>
 struct ShrinkWave {
-    static constexpr int NB = R >= 16 ? R / 16 : 1;
-    static constexpr int KB = R <= 16 ? 4 : (R == 32 ? 2 : 1);
+    static constexpr int NB = R >= 16 ? R / 16 : 1;            // weight tiles per K unit
+    static constexpr int XN = R == 8 ? 2 : 1;                  // x operands per K unit
+    static constexpr int NACC = R == 8 ? 2 : NB;               // accumulators per projection
+    static constexpr int KU = R == 8 ? 64 : 32;                // K values per unit
+    static constexpr int KB = R <= 16 ? (R == 8 ? 2 : 4) : (R == 32 ? 2 : 1);   // units per step
 
     int lane, g, i16, h_in;
     const uint16_t *Ap[NPROJ];
     const uint16_t *xp;      // this lane's x row (a valid row even if the lane's row is not)
     bool row_ok;
-    f32x4 acc[NPROJ][NB];
+    f32x4 acc[NPROJ][NACC];
 
-    // All loads are unconditional: a K-block beyond the wave's range re-reads the last valid
-    // block and a row beyond the tile re-reads the tile's first row; both are then replaced
+    struct Step {
+        u32x4 w[NPROJ][KB][NB];
+        u32x4 x[KB][XN];
+    };
+
+    // All loads are unconditional: a K unit beyond the wave's range re-reads the last valid
+    // unit and a row beyond the tile re-reads the tile's first row; both are then replaced
     // by zeros with selects.  No branches, so the next step's loads stay in flight.
-    __device__ inline void load(int kb0, int kb_end, u32x4 (&w)[NPROJ][KB][NB], u32x4 (&xv)[KB]) const
+    __device__ inline void load(int kb0, int kb_end, Step &s) const
     {
         const u32x4 zero4 = {0u, 0u, 0u, 0u};
 #pragma unroll
@@ -40,42 +56,78 @@ struct ShrinkWave {
             for (int pj = 0; pj < NPROJ; ++pj)
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb) {
-                    u32x4 t;
-                    if (R >= 16) t = ld16<NT>(Ap[pj] + (((int64_t)kb * NB + nb) * 64 + lane) * 8);
-                    else t = ld16<NT>(Ap[pj] + ((int64_t)kb * 32 + g * 8 + (i16 & 7)) * 8);
-                    w[pj][u][nb] = (k_ok && (R >= 16 || i16 < 8)) ? t : zero4;
+                    const u32x4 t = ld16<NT>(Ap[pj] + (((int64_t)kb * NB + nb) * 64 + lane) * 8);
+                    s.w[pj][u][nb] = k_ok ? t : zero4;
                 }
-            const bool c_ok = kb * kKBlock + g * 8 < h_in;
-            const u32x4 t = ld16<false>(xp + (c_ok ? kb * kKBlock + g * 8 : 0));
-            xv[u] = (k_ok && row_ok && c_ok) ? t : zero4;
+#pragma unroll
+            for (int h = 0; h < XN; ++h) {
+                const int c = kb * KU + h * 32 + g * 8;
+                const bool c_ok = c < h_in;
+                const u32x4 t = ld16<false>(xp + (c_ok ? c : 0));
+                s.x[u][h] = (k_ok && row_ok && c_ok) ? t : zero4;
+            }
         }
     }
 
-    __device__ inline void mma(const u32x4 (&w)[NPROJ][KB][NB], const u32x4 (&xv)[KB])
+    __device__ inline void mma(const Step &s)
     {
 #pragma unroll
         for (int u = 0; u < KB; ++u)
 #pragma unroll
-            for (int pj = 0; pj < NPROJ; ++pj)
+            for (int pj = 0; pj < NPROJ; ++pj) {
+                if (R == 8) {
 #pragma unroll
-                for (int nb = 0; nb < NB; ++nb)
-                    acc[pj][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                        as_bf16x8(w[pj][u][nb]), as_bf16x8(xv[u]), acc[pj][nb], 0, 0, 0);
+                    for (int h = 0; h < 2; ++h)
+                        acc[pj][h] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                            as_bf16x8(s.w[pj][u][0]), as_bf16x8(s.x[u][h]), acc[pj][h], 0, 0, 0);
+                } else {
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb)
+                        acc[pj][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                            as_bf16x8(s.w[pj][u][nb]), as_bf16x8(s.x[u][0]), acc[pj][nb], 0, 0, 0);
+                }
+            }
+    }
+
+    // K units [kb_begin, kb_end), two steps in flight
+    __device__ inline void run(int kb_begin, int kb_end)
+    {
+#pragma unroll
+        for (int pj = 0; pj < NPROJ; ++pj)
+#pragma unroll
+            for (int a = 0; a < NACC; ++a) acc[pj][a] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (kb_begin >= kb_end) return;
+        Step s0, s1;
+        load(kb_begin, kb_end, s0);
+        int kb0 = kb_begin;
+        for (; kb0 + 2 * KB < kb_end; kb0 += 2 * KB) {
+            load(kb0 + KB, kb_end, s1);
+            mma(s0);
+            load(kb0 + 2 * KB, kb_end, s0);
+            mma(s1);
+        }
+        if (kb0 + KB < kb_end) {
+            load(kb0 + KB, kb_end, s1);
+            mma(s0);
+            mma(s1);
+        } else {
+            mma(s0);
+        }
     }
 };
 
 // tiles, units and counts are passed again as restrict-qualified kernel arguments: with a
-// workgroup-uniform index the compiler then reads them through the scalar cache, which
-// shortens the dependent chain tile -> unit -> first data load.
-template <int R, int NPROJ, bool NT>
+// uniform index the compiler then reads them through the scalar cache, which shortens the
+// dependent chain tile -> unit -> first data load.
+template <int R, int NPROJ, bool NT, bool WPT>
 __global__ __launch_bounds__(256, 2) void shrink16_kernel(ShrinkParams p,
                                                           const lora_tile *__restrict__ tiles,
                                                           const Unit *__restrict__ units,
                                                           const int32_t *__restrict__ counts)
 {
     using Wave = ShrinkWave<R, NPROJ, NT>;
-    constexpr int NB = Wave::NB, KB = Wave::KB;
-    __shared__ f32x4 red[4][NPROJ][NB][64];
+    constexpr int NACC = Wave::NACC, KU = Wave::KU;
+    __shared__ f32x4 red[WPT ? 1 : 4][NPROJ][NACC][WPT ? 1 : 64];
 
     const int tid = threadIdx.x, wave = tid >> 6;
     Wave w;
@@ -85,10 +137,12 @@ __global__ __launch_bounds__(256, 2) void shrink16_kernel(ShrinkParams p,
     w.h_in = p.h_in;
     const int n_tiles = counts[2];
     const int n_items = n_tiles * p.n_parts;
-    const int kblocks = (p.h_in + kKBlock - 1) / kKBlock;
-    const int kb_per_wave = (p.kb_per_part + 3) >> 2;
+    const int kblocks = (p.h_in + KU - 1) / KU;
 
-    for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
+    // item loop: a workgroup's item in the K-split form, a wave's item otherwise
+    const int first = WPT ? __builtin_amdgcn_readfirstlane(blockIdx.x * 4 + wave) : blockIdx.x;
+    const int stride = WPT ? gridDim.x * 4 : gridDim.x;
+    for (int item = first; item < n_items; item += stride) {
         const int tile_ix = item / p.n_parts;
         const int part = item - tile_ix * p.n_parts;
         const lora_tile t = tiles[tile_ix];
@@ -101,61 +155,78 @@ __global__ __launch_bounds__(256, 2) void shrink16_kernel(ShrinkParams p,
             if (p.src_row) s = p.src_row[s];
             w.xp = p.x + (int64_t)s * p.ldx;
         }
-        const int part_end = min((part + 1) * p.kb_per_part, kblocks);
-        const int kb_begin = part * p.kb_per_part + wave * kb_per_wave;
-        const int kb_end = min(kb_begin + kb_per_wave, part_end);
-#pragma unroll
-        for (int pj = 0; pj < NPROJ; ++pj)
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb) w.acc[pj][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+        const int part_begin = part * p.kb_per_part;
+        const int part_end = min(part_begin + p.kb_per_part, kblocks);
 
-        if (kb_begin < kb_end) {
-            u32x4 w0[NPROJ][KB][NB], x0[KB], w1[NPROJ][KB][NB], x1[KB];
-            w.load(kb_begin, kb_end, w0, x0);
-            for (int kb0 = kb_begin; kb0 < kb_end; kb0 += 2 * KB) {
-                const bool has1 = kb0 + KB < kb_end;
-                if (has1) w.load(kb0 + KB, kb_end, w1, x1);
-                w.mma(w0, x0);
-                if (has1) {
-                    if (kb0 + 2 * KB < kb_end) w.load(kb0 + 2 * KB, kb_end, w0, x0);
-                    w.mma(w1, x1);
+        if (WPT) {
+            w.run(part_begin, part_end);
+            // lane (row i16, group g) holds rank entries 4g..4g+3 of its row; for rank 8 the
+            // entries of groups 2,3 belong to the second half product and are added to the
+            // first half's entries held 32 lanes below
+#pragma unroll
+            for (int pj = 0; pj < NPROJ; ++pj) {
+                if (R == 8) {
+                    f32x4 s = w.acc[pj][0];
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) s[q] += __shfl_down(w.acc[pj][1][q], 32, 64);
+                    if (w.row_ok && w.g < 2)
+                        st16f(p.v[pj] + ((int64_t)part * p.P + t.row0 + w.i16) * R + w.g * 4, s);
+                } else {
+#pragma unroll
+                    for (int nb = 0; nb < Wave::NB; ++nb)
+                        if (w.row_ok)
+                            st16f(p.v[pj] + ((int64_t)part * p.P + t.row0 + w.i16) * R + nb * 16 + w.g * 4,
+                                  w.acc[pj][nb]);
                 }
             }
-        }
+        } else {
+            const int kb_per_wave = (p.kb_per_part + 3) >> 2;
+            const int kb_begin = part_begin + wave * kb_per_wave;
+            w.run(kb_begin, min(kb_begin + kb_per_wave, part_end));
 
-        // add the four waves' sums in a fixed order and store this part of v
+            // add the four waves' sums in a fixed order and store this part of v
 #pragma unroll
-        for (int pj = 0; pj < NPROJ; ++pj)
+            for (int pj = 0; pj < NPROJ; ++pj)
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb) red[wave][pj][nb][w.lane] = w.acc[pj][nb];
-        __syncthreads();
-        constexpr int NOUT = NPROJ * NB * 64;
-        for (int o = tid; o < NOUT; o += 256) {
-            const int l = o & 63;
-            const int nb = (o >> 6) % NB;
-            const int pj = (o >> 6) / NB;
-            const int row = l & 15;
-            const int j = nb * 16 + (l >> 4) * 4;
-            if (row < t.n_rows && j < R) {
-                f32x4 s = red[0][pj][nb][l];
-                s += red[1][pj][nb][l];
-                s += red[2][pj][nb][l];
-                s += red[3][pj][nb][l];
-                float *dst = p.v[pj] + ((int64_t)part * p.P + t.row0 + row) * R + j;
-                st16f(dst, s);
+                for (int a = 0; a < NACC; ++a) red[wave][pj][a][w.lane] = w.acc[pj][a];
+            __syncthreads();
+            constexpr int NOUT = NPROJ * (R == 8 ? 1 : NACC) * 64;
+            for (int o = tid; o < NOUT; o += 256) {
+                const int l = o & 63;
+                const int a = R == 8 ? 0 : (o >> 6) % NACC;
+                const int pj = R == 8 ? (o >> 6) : (o >> 6) / NACC;
+                const int row = l & 15;
+                const int j = a * 16 + (l >> 4) * 4;
+                if (row < t.n_rows && j < R) {
+                    f32x4 s;
+                    if (R == 8) {
+                        s = red[0][pj][0][l] + red[0][pj][1][l + 32];
+                        s += red[1][pj][0][l] + red[1][pj][1][l + 32];
+                        s += red[2][pj][0][l] + red[2][pj][1][l + 32];
+                        s += red[3][pj][0][l] + red[3][pj][1][l + 32];
+                    } else {
+                        s = red[0][pj][a][l];
+                        s += red[1][pj][a][l];
+                        s += red[2][pj][a][l];
+                        s += red[3][pj][a][l];
+                    }
+                    st16f(p.v[pj] + ((int64_t)part * p.P + t.row0 + row) * R + j, s);
+                }
             }
+            __syncthreads();
         }
-        __syncthreads();
     }
 }
 
 template <int R, int NPROJ>
 hipError_t launch_rn(const ShrinkParams &p, hipStream_t s)
 {
-    if (p.nontemporal)
-        hipLaunchKernelGGL((shrink16_kernel<R, NPROJ, true>), dim3(p.grid), dim3(256), 0, s, p, p.tiles, p.units, p.counts);
+    if (p.wave_per_tile)
+        hipLaunchKernelGGL((shrink16_kernel<R, NPROJ, true, true>), dim3(p.grid), dim3(256), 0, s, p,
+                           p.tiles, p.units, p.counts);
     else
-        hipLaunchKernelGGL((shrink16_kernel<R, NPROJ, false>), dim3(p.grid), dim3(256), 0, s, p, p.tiles, p.units, p.counts);
+        hipLaunchKernelGGL((shrink16_kernel<R, NPROJ, true, false>), dim3(p.grid), dim3(256), 0, s, p,
+                           p.tiles, p.units, p.counts);
     return hipGetLastError();
 }
 

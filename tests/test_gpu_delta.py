@@ -95,6 +95,18 @@ def test_segment_lengths_around_tile_boundaries(tokens):
     check_accumulate(got, res, f"{tokens} rows")
 
 
+@pytest.mark.parametrize("rank,h_in", [(8, 200), (8, 64), (16, 200), (32, 104), (64, 72)])
+def test_thousands_of_small_tiles_one_wave_per_tile(rank, h_in):
+    """More than 4096 tiles over a short K range: the shrink runs one wave per tile with the
+    K range not split (one K part)."""
+    w = dense_workload(rank, h_in, 136, n=4400, tokens=4500)
+    b, ws, got, (dp, db, run) = run_dense(w, 21, "normal", drop=0.02)
+    assert L.lora_v_bytes(dp.pool, 0, 4500) < 2 * 4500 * rank * 4      # a single K part
+    assert int(db.seg.counts.cpu()[2]) > 2000
+    res = oracle_projection(b, ws, 0, 0)
+    check_accumulate(got, res, f"wave per tile r{rank}")
+
+
 def test_shrink_output_matches_oracle_v_and_src_row():
     w = dense_workload(16, 2080, 136, n=4, tokens=72)
     b = W.make_batch(w, 16, hetero_scale=True)

@@ -43,7 +43,7 @@ def indices(exe, which, h, r):
 
 @pytest.mark.parametrize("r", [8, 16, 32, 64])
 def test_packA_is_a_bijection_with_contiguous_k_runs(exe, r):
-    h = 96
+    h = 128
     ix = indices(exe, 0, h, r).reshape(h, r)
     assert sorted(ix.ravel().tolist()) == list(range(h * r))
     # eight consecutive K values of one rank index are contiguous and 16-byte aligned
@@ -51,10 +51,11 @@ def test_packA_is_a_bijection_with_contiguous_k_runs(exe, r):
         for j in range(r):
             run = ix[c0:c0 + 8, j]
             assert run[0] % 8 == 0 and np.array_equal(run, run[0] + np.arange(8))
-    # one 32-deep K block of 16 rank indices (or all 8) is one contiguous span
-    span = 32 * min(r, 16)
-    blk = ix[0:32, 0:min(r, 16)]
-    assert blk.min() == 0 and blk.max() == span - 1
+    # one K block (32 deep, 64 for rank 8) of 16 rank indices (or all 8) is one contiguous 1 KiB
+    depth = 64 if r == 8 else 32
+    span = depth * min(r, 16)
+    blk = ix[0:depth, 0:min(r, 16)]
+    assert span == 512 and blk.min() == 0 and blk.max() == span - 1
 
 
 @pytest.mark.parametrize("r", [8, 16, 32, 64])
