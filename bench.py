@@ -83,20 +83,16 @@ def make_phases(L, W, dp, db, run, acct):
                                             db.y["down"].shape[1], run.ws),
             S * r * d.h_out * 2 + P_act * d.h_out * 4))
     else:
+        # one call per run of projections that share an input (q/k/v, gate/up): a shrink launch
+        # and an expand launch for the whole group
         seen = set()
-        for j, p in enumerate(w.projs):
-            x, y = db.inputs[p.input], db.y[p.name]
-            xb = 0 if p.input in seen else P_act * p.h_in * 2
-            seen.add(p.input)
-            phases.append(Phase(
-                f"{p.name}_shrink",
-                lambda layer, j=j, x=x: L.lora_shrink(pool, layer, j, x, x.shape[1], None, seg, run.v),
-                S * r * p.h_in * 2 + xb))
-            phases.append(Phase(
-                f"{p.name}_expand",
-                lambda layer, j=j, y=y: L.lora_expand(pool, layer, j, run.v, seg, y, y.shape[1],
-                                                      L.LORA_DTYPE_BF16),
-                S * r * p.h_out * 2 + P_act * p.h_out * 4))
+        for j, c in run.groups:
+            projs = w.projs[j:j + c]
+            xb = 0 if projs[0].input in seen else P_act * projs[0].h_in * 2
+            seen.add(projs[0].input)
+            nbytes = xb + sum(S * r * (p.h_in + p.h_out) * 2 + P_act * p.h_out * 4 for p in projs)
+            phases.append(Phase("+".join(p.name for p in projs) + "_apply",
+                                lambda layer, j=j, c=c: run.apply_group(layer, j, c), nbytes))
     return phases
 
 

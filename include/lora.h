@@ -202,6 +202,31 @@ int lora_shrink(const lora_pool *pool, int layer, int proj, const void *x, int64
 int lora_expand(const lora_pool *pool, int layer, int proj, const float *v,
                 const lora_segments *seg, void *y, int64_t ldy, int out_dtype, void *stream);
 
+/*
+ * lora_apply: the whole delta of one projection, y[row] += scale * (x[row] * A) * B (Sec. 2.2):
+ * exactly lora_shrink followed by lora_expand on the workspace v (lora_v_bytes(pool, proj, P)
+ * bytes, contents unspecified afterwards), with the arguments of the two.
+ */
+int lora_apply(const lora_pool *pool, int layer, int proj, const void *x, int64_t ldx,
+               const int32_t *src_row, const lora_segments *seg, void *y, int64_t ldy,
+               int out_dtype, float *v, void *stream);
+
+/*
+ * lora_apply_group: the deltas of n_proj (1 .. 3) consecutive projections proj0 .. proj0+n_proj-1
+ * that read the same input x (equal h_in; their h_out may differ): the query/key/value
+ * projections of an attention block, or gate and up (Sec. 2.3 lists the per-expert matrices
+ * that share the expert's input).  Results are bit-identical to n_proj lora_apply calls; x is
+ * read once per row tile for all of them and each phase is one launch for the group when the
+ * batch is a decode batch.  y[j], ldy[j]: output and row stride of projection proj0 + j (host
+ * arrays of n_proj entries).  ws: device scratch of lora_group_ws_bytes(pool, proj0, n_proj, P).
+ */
+size_t lora_group_ws_bytes(const lora_pool *pool, int proj0, int n_proj, int P);
+
+int lora_apply_group(const lora_pool *pool, int layer, int proj0, int n_proj, const void *x,
+                     int64_t ldx, const int32_t *src_row, const lora_segments *seg,
+                     void *const *y, const int64_t *ldy, int out_dtype, void *ws,
+                     size_t ws_bytes, void *stream);
+
 /* ------------------------------------------------------------------------------------
  * MoE application (Sec. 3: the LoRA computation runs twice per MoE layer, for the
  * up/gate and for the down projection; Sec. 4.1: a batch of b requests with top-k routing

@@ -20,7 +20,7 @@ EXPORTED_SYMBOLS = [
     "lora_pool_load_unit", "lora_pool_load_adapter_layer", "lora_pool_read_unit",
     "lora_pool_unit_layout", "lora_pool_device_table", "lora_pool_destroy",
     "lora_segments_ws_bytes", "lora_build_segments", "lora_v_bytes", "lora_shrink",
-    "lora_expand", "lora_moe_ws_bytes", "lora_moe_apply", "lora_moe_shrink", "lora_moe_expand",
+    "lora_expand", "lora_apply", "lora_group_ws_bytes", "lora_apply_group", "lora_moe_ws_bytes", "lora_moe_apply", "lora_moe_shrink", "lora_moe_expand",
 ]
 
 
@@ -103,6 +103,13 @@ def load_library():
     lib.lora_shrink.argtypes = [vp, i32, i32, vp, i64, vp, C.POINTER(_Segments), vp, vp]
     lib.lora_expand.restype = i32
     lib.lora_expand.argtypes = [vp, i32, i32, vp, C.POINTER(_Segments), vp, i64, i32, vp]
+    lib.lora_apply.restype = i32
+    lib.lora_apply.argtypes = [vp, i32, i32, vp, i64, vp, C.POINTER(_Segments), vp, i64, i32, vp, vp]
+    lib.lora_group_ws_bytes.restype = sz
+    lib.lora_group_ws_bytes.argtypes = [vp, i32, i32, i32]
+    lib.lora_apply_group.restype = i32
+    lib.lora_apply_group.argtypes = [vp, i32, i32, i32, vp, i64, vp, C.POINTER(_Segments),
+                                     C.POINTER(vp), C.POINTER(i64), i32, vp, sz, vp]
     lib.lora_moe_ws_bytes.restype = sz
     lib.lora_moe_ws_bytes.argtypes = [vp, i32]
     lib.lora_moe_apply.restype = i32
@@ -306,6 +313,29 @@ def lora_expand(pool, layer, proj, v, seg: Segments, y, ldy, out_dtype=LORA_DTYP
                 stream=None):
     _check(load_library().lora_expand(_h(pool), layer, proj, _addr(v), C.byref(seg.c), _addr(y),
                                       ldy, out_dtype, _stream(stream)), "lora_expand")
+
+
+def lora_apply(pool, layer, proj, x, ldx, src_row, seg: Segments, y, ldy, v,
+               out_dtype=LORA_DTYPE_BF16, stream=None):
+    _check(load_library().lora_apply(_h(pool), layer, proj, _addr(x), ldx, _addr(src_row),
+                                     C.byref(seg.c), _addr(y), ldy, out_dtype, _addr(v),
+                                     _stream(stream)), "lora_apply")
+
+
+def lora_group_ws_bytes(pool, proj0: int, n_proj: int, P: int) -> int:
+    return int(load_library().lora_group_ws_bytes(_h(pool), proj0, n_proj, P))
+
+
+def lora_apply_group(pool, layer, proj0, x, ldx, src_row, seg: Segments, ys, ldys, ws,
+                     out_dtype=LORA_DTYPE_BF16, stream=None):
+    """ys / ldys: one output tensor and row stride per projection of the group."""
+    n = len(ys)
+    y_arr = (C.c_void_p * n)(*[_addr(y) for y in ys])
+    ld_arr = (C.c_int64 * n)(*[int(v) for v in ldys])
+    _check(load_library().lora_apply_group(_h(pool), layer, proj0, n, _addr(x), ldx, _addr(src_row),
+                                           C.byref(seg.c), y_arr, ld_arr, out_dtype, _addr(ws),
+                                           ws.numel() * ws.element_size(), _stream(stream)),
+           "lora_apply_group")
 
 
 def lora_moe_ws_bytes(pool, P: int) -> int:

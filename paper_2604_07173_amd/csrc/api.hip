@@ -225,25 +225,30 @@ int check_segments(const lora_segments *s)
     return LORA_OK;
 }
 
-int do_shrink(const lora_pool *pool, int layer, int proj0, int n_fused, const void *x, int64_t ldx,
-              const int32_t *src_row, const lora_segments *seg, float *v0, float *v1, hipStream_t st)
+// A group of n consecutive projections proj0 .. proj0+n-1 that read the same input (same
+// h_in): per projection its slice of the intermediate, its output and the output's stride.
+struct Group {
+    int proj0, n;
+    float *v[kMaxFused];
+    void *y[kMaxFused];
+    int64_t ldy[kMaxFused];
+};
+
+int do_shrink(const lora_pool *pool, int layer, const Group &g, const void *x, int64_t ldx,
+              const int32_t *src_row, const lora_segments *seg, hipStream_t st)
 {
-    const lora_proj_desc &pd = pool->d.proj[proj0];
-    const KSplit ks = ksplit_of(pool, proj0, seg->P);
+    const lora_proj_desc &pd = pool->d.proj[g.proj0];
+    const KSplit ks = ksplit_of(pool, g.proj0, seg->P);
     ShrinkParams sp;
     memset(&sp, 0, sizeof sp);
     sp.units = pool->device_table() + pool->table_index(layer, 0, 0, 0);
     sp.n_proj = pool->d.n_proj;
-    sp.proj0 = proj0;
-    sp.n_fused = n_fused;
     sp.x = static_cast<const uint16_t *>(x);
     sp.ldx = ldx;
     sp.src_row = src_row;
     sp.perm = seg->perm;
     sp.tiles = seg->tiles;
     sp.counts = seg->counts;
-    sp.v[0] = v0;
-    sp.v[1] = v1;
     sp.P = seg->P;
     sp.h_in = pd.h_in;
     sp.n_parts = ks.n_parts;
@@ -254,83 +259,125 @@ int do_shrink(const lora_pool *pool, int layer, int proj0, int n_fused, const vo
     const int64_t items = tiles_upper_bound(pool, seg->P, seg->tile_rows) * ks.n_parts;
     if (seg->tile_rows == kDecodeTileRows) {
         static const int per_cu = env_int("LORA_DEC_SHRINK_WGS_PER_CU", 8, 1, 64);
+        sp.proj0 = g.proj0;
+        sp.n_fused = g.n;
+        for (int j = 0; j < g.n; ++j) sp.v[j] = g.v[j];
         sp.wave_per_tile = ks.wave_per_tile;
         const int64_t wgs = ks.wave_per_tile ? (items + 3) / 4 : items;
         sp.grid = (int)std::min<int64_t>(wgs, (int64_t)cu_count() * per_cu);
         LORA_HIP(launch_shrink_decode(sp, st));
         return LORA_OK;
     }
+    // 32-row tiles: at most two projections per launch
     static const int per_cu = env_int("LORA_SHRINK_WGS_PER_CU", 4, 1, 64);
     sp.grid = (int)std::min<int64_t>(items, (int64_t)cu_count() * per_cu);
-    LORA_HIP(launch_shrink(sp, st));
+    for (int j = 0; j < g.n; j += 2) {
+        sp.proj0 = g.proj0 + j;
+        sp.n_fused = std::min(2, g.n - j);
+        sp.v[0] = g.v[j];
+        sp.v[1] = sp.n_fused == 2 ? g.v[j + 1] : nullptr;
+        LORA_HIP(launch_shrink(sp, st));
+    }
     return LORA_OK;
 }
 
-int do_expand(const lora_pool *pool, int layer, int proj0, int n_fused, const float *v0,
-              const float *v1, const lora_segments *seg, void *y0, void *y1, int64_t ldy,
+int do_expand(const lora_pool *pool, int layer, const Group &g, const lora_segments *seg,
               int out_dtype, hipStream_t st)
 {
-    const lora_proj_desc &pd = pool->d.proj[proj0];
-    const KSplit ks = ksplit_of(pool, proj0, seg->P);
+    const KSplit ks = ksplit_of(pool, g.proj0, seg->P);
     ExpandParams ep;
     memset(&ep, 0, sizeof ep);
     ep.units = pool->device_table() + pool->table_index(layer, 0, 0, 0);
     ep.n_proj = pool->d.n_proj;
-    ep.proj0 = proj0;
-    ep.n_fused = n_fused;
-    ep.v[0] = v0;
-    ep.v[1] = v1;
     ep.n_parts = ks.n_parts;
     ep.P = seg->P;
     ep.perm = seg->perm;
     ep.tiles = seg->tiles;
     ep.counts = seg->counts;
-    ep.y[0] = y0;
-    ep.y[1] = y1;
-    ep.ldy = ldy;
-    ep.h_out = pd.h_out;
-    ep.n_chunks = chunks_of(pd.h_out);
-    // waves per workgroup: the largest of 4, 3, 2 that divides the chunk count, else 4
-    ep.waves = 4;
-    if (ep.n_chunks % 4 != 0) {
-        if (ep.n_chunks % 3 == 0) ep.waves = 3;
-        else if (ep.n_chunks % 2 == 0) ep.waves = 2;
-        else if (ep.n_chunks < 4) ep.waves = ep.n_chunks;
-    }
     ep.out_f32 = out_dtype == LORA_DTYPE_F32;
     ep.rank = pool->d.rank;
     static const int nt = env_int("LORA_NONTEMPORAL", 1, 0, 1);
     ep.nontemporal = nt;
     const int64_t tub = std::max<int64_t>(1, tiles_upper_bound(pool, seg->P, seg->tile_rows));
     if (seg->tile_rows == kDecodeTileRows) {
-        // every wave works alone: slices of about chunks_per_item chunks per (tile, projection)
+        // every wave works alone on wave items = (tile, projection, slice of 128-column chunks);
         // chunks per wave item: long enough to amortise the per-item prologue, short enough
         // that a small batch still yields a few thousand wave items
         static const int cpi_max = env_int("LORA_DEC_CHUNKS_PER_ITEM", 8, 1, 4096);
         static const int want_items = env_int("LORA_DEC_EXPAND_ITEMS", 4096, 1, 1 << 22);
         static const int per_cu = env_int("LORA_DEC_EXPAND_WGS_PER_CU", 4, 1, 64);
-        const int64_t units = tub * n_fused * ep.n_chunks;
+        ep.proj0 = g.proj0;
+        ep.n_fused = g.n;
+        int64_t chunks_per_tile = 0;
+        for (int j = 0; j < g.n; ++j) chunks_per_tile += chunks_of(pool->d.proj[g.proj0 + j].h_out);
+        const int64_t units = tub * chunks_per_tile;
         const int cpi = (int)std::max<int64_t>(1, std::min<int64_t>(cpi_max, units / want_items));
+        ep.slice0[0] = 0;
+        for (int j = 0; j < g.n; ++j) {
+            ep.v[j] = g.v[j];
+            ep.y[j] = g.y[j];
+            ep.ldy[j] = g.ldy[j];
+            ep.h_out[j] = pool->d.proj[g.proj0 + j].h_out;
+            ep.n_chunks[j] = chunks_of(ep.h_out[j]);
+            // no empty slice: a row is cut into n_slices pieces of ceil(n_chunks / n_slices) chunks
+            const int want = std::max(1, (ep.n_chunks[j] + cpi - 1) / cpi);
+            const int cps = (ep.n_chunks[j] + want - 1) / want;
+            ep.n_slices[j] = (ep.n_chunks[j] + cps - 1) / cps;
+            ep.slice0[j + 1] = ep.slice0[j] + ep.n_slices[j];
+        }
+        for (int j = g.n; j < kMaxFused; ++j) ep.slice0[j + 1] = ep.slice0[g.n];
         ep.waves = 4;
-        ep.n_slices = std::max(1, (ep.n_chunks + cpi - 1) / cpi);
-        const int64_t wave_items = tub * n_fused * ep.n_slices;
+        const int64_t wave_items = tub * ep.slice0[g.n];
         ep.grid = (int)std::min<int64_t>((wave_items + ep.waves - 1) / ep.waves,
                                          (int64_t)cu_count() * per_cu);
         LORA_HIP(launch_expand_decode(ep, st));
         return LORA_OK;
     }
     // general kernel: a workgroup walks over tile_group consecutive tiles with one chunk per
-    // wave held in registers; the group is as long as still leaves enough workgroups
-    const int cgroups = (ep.n_chunks + ep.waves - 1) / ep.waves;
+    // wave held in registers; projections of equal width go two per launch
     static const int target = env_int("LORA_EXPAND_ITEMS", 1536, 1, 1 << 20);
     static const int tg_max = env_int("LORA_EXPAND_TILE_GROUP", 1, 1, 1024);
-    ep.tile_group = (int)std::max<int64_t>(1, std::min<int64_t>(tg_max, tub * n_fused * cgroups / target));
-    ep.n_slices = 1;
     static const int per_cu = env_int("LORA_EXPAND_WGS_PER_CU", 8, 1, 64);
-    const int64_t items = ((tub + ep.tile_group - 1) / ep.tile_group) * n_fused * cgroups;
-    ep.grid = (int)std::min<int64_t>(items, (int64_t)cu_count() * per_cu);
-    LORA_HIP(launch_expand(ep, st));
+    for (int j = 0; j < g.n;) {
+        const int h_out = pool->d.proj[g.proj0 + j].h_out;
+        const int nf = (j + 1 < g.n && pool->d.proj[g.proj0 + j + 1].h_out == h_out) ? 2 : 1;
+        ep.proj0 = g.proj0 + j;
+        ep.n_fused = nf;
+        for (int q = 0; q < nf; ++q) {
+            ep.v[q] = g.v[j + q];
+            ep.y[q] = g.y[j + q];
+            ep.ldy[q] = g.ldy[j + q];
+            ep.h_out[q] = h_out;
+            ep.n_chunks[q] = chunks_of(h_out);
+        }
+        const int n_chunks = ep.n_chunks[0];
+        // waves per workgroup: the largest of 4, 3, 2 that divides the chunk count, else 4
+        ep.waves = 4;
+        if (n_chunks % 4 != 0) {
+            if (n_chunks % 3 == 0) ep.waves = 3;
+            else if (n_chunks % 2 == 0) ep.waves = 2;
+            else if (n_chunks < 4) ep.waves = n_chunks;
+        }
+        const int cgroups = (n_chunks + ep.waves - 1) / ep.waves;
+        ep.tile_group = (int)std::max<int64_t>(1, std::min<int64_t>(tg_max, tub * nf * cgroups / target));
+        const int64_t items = ((tub + ep.tile_group - 1) / ep.tile_group) * nf * cgroups;
+        ep.grid = (int)std::min<int64_t>(items, (int64_t)cu_count() * per_cu);
+        LORA_HIP(launch_expand(ep, st));
+        j += nf;
+    }
     return LORA_OK;
+}
+
+Group single(int proj, float *v, void *y, int64_t ldy)
+{
+    Group g;
+    memset(&g, 0, sizeof g);
+    g.proj0 = proj;
+    g.n = 1;
+    g.v[0] = v;
+    g.y[0] = y;
+    g.ldy[0] = ldy;
+    return g;
 }
 
 int check_act(const void *ptr, int64_t ld, int width, size_t elem)
@@ -643,7 +690,7 @@ int lora_shrink(const lora_pool *pool, int layer, int proj, const void *x, int64
     if (rc != LORA_OK) return rc;
     if (!v) return LORA_ERR_INVALID_ARG;
     if (!aligned(v, 16)) return LORA_ERR_MISALIGNED;
-    return do_shrink(pool, layer, proj, 1, x, ldx, src_row, seg, v, nullptr,
+    return do_shrink(pool, layer, single(proj, v, nullptr, 0), x, ldx, src_row, seg,
                      static_cast<hipStream_t>(stream));
 }
 
@@ -662,8 +709,80 @@ int lora_expand(const lora_pool *pool, int layer, int proj, const float *v,
     if (rc != LORA_OK) return rc;
     if (!v) return LORA_ERR_INVALID_ARG;
     if (!aligned(v, 16)) return LORA_ERR_MISALIGNED;
-    return do_expand(pool, layer, proj, 1, v, nullptr, seg, y, nullptr, ldy, out_dtype,
+    return do_expand(pool, layer, single(proj, const_cast<float *>(v), y, ldy), seg, out_dtype,
                      static_cast<hipStream_t>(stream));
+}
+
+int lora_apply(const lora_pool *pool, int layer, int proj, const void *x, int64_t ldx,
+               const int32_t *src_row, const lora_segments *seg, void *y, int64_t ldy, int out_dtype,
+               float *v, void *stream)
+{
+    int rc = check_pool(pool);
+    if (rc != LORA_OK) return rc;
+    rc = check_segments(seg);
+    if (rc != LORA_OK) return rc;
+    if (layer < 0 || layer >= pool->d.n_layers || proj < 0 || proj >= pool->d.n_proj)
+        return LORA_ERR_BAD_SHAPE;
+    if (out_dtype != LORA_DTYPE_BF16 && out_dtype != LORA_DTYPE_F32) return LORA_ERR_INVALID_ARG;
+    if (seg->P == 0) return LORA_OK;
+    rc = check_act(x, ldx, pool->d.proj[proj].h_in, 2);
+    if (rc != LORA_OK) return rc;
+    rc = check_act(y, ldy, pool->d.proj[proj].h_out, out_dtype == LORA_DTYPE_F32 ? 4 : 2);
+    if (rc != LORA_OK) return rc;
+    if (!v) return LORA_ERR_INVALID_ARG;
+    if (!aligned(v, 16)) return LORA_ERR_MISALIGNED;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const Group g = single(proj, v, y, ldy);
+    rc = do_shrink(pool, layer, g, x, ldx, src_row, seg, st);
+    if (rc != LORA_OK) return rc;
+    return do_expand(pool, layer, g, seg, out_dtype, st);
+}
+
+size_t lora_group_ws_bytes(const lora_pool *pool, int proj0, int n_proj, int P)
+{
+    if (check_pool(pool) != LORA_OK || proj0 < 0 || n_proj < 1 || proj0 + n_proj > pool->d.n_proj || P < 0)
+        return 0;
+    return (size_t)n_proj * lora_v_bytes(pool, proj0, P);
+}
+
+int lora_apply_group(const lora_pool *pool, int layer, int proj0, int n_proj, const void *x,
+                     int64_t ldx, const int32_t *src_row, const lora_segments *seg, void *const *y,
+                     const int64_t *ldy, int out_dtype, void *ws, size_t ws_bytes, void *stream)
+{
+    int rc = check_pool(pool);
+    if (rc != LORA_OK) return rc;
+    rc = check_segments(seg);
+    if (rc != LORA_OK) return rc;
+    const lora_pool_desc &d = pool->d;
+    if (n_proj < 1 || n_proj > kMaxFused) return LORA_ERR_INVALID_ARG;
+    if (layer < 0 || layer >= d.n_layers || proj0 < 0 || proj0 + n_proj > d.n_proj)
+        return LORA_ERR_BAD_SHAPE;
+    for (int j = 1; j < n_proj; ++j)
+        if (d.proj[proj0 + j].h_in != d.proj[proj0].h_in) return LORA_ERR_BAD_SHAPE;
+    if (out_dtype != LORA_DTYPE_BF16 && out_dtype != LORA_DTYPE_F32) return LORA_ERR_INVALID_ARG;
+    if (!y || !ldy) return LORA_ERR_INVALID_ARG;
+    if (seg->P == 0) return LORA_OK;
+    rc = check_act(x, ldx, d.proj[proj0].h_in, 2);
+    if (rc != LORA_OK) return rc;
+    if (!ws) return LORA_ERR_INVALID_ARG;
+    if (!aligned(ws, 16)) return LORA_ERR_MISALIGNED;
+    if (ws_bytes < lora_group_ws_bytes(pool, proj0, n_proj, seg->P)) return LORA_ERR_BUFFER_TOO_SMALL;
+    Group g;
+    memset(&g, 0, sizeof g);
+    g.proj0 = proj0;
+    g.n = n_proj;
+    const size_t vb = lora_v_bytes(pool, proj0, seg->P);
+    for (int j = 0; j < n_proj; ++j) {
+        rc = check_act(y[j], ldy[j], d.proj[proj0 + j].h_out, out_dtype == LORA_DTYPE_F32 ? 4 : 2);
+        if (rc != LORA_OK) return rc;
+        g.v[j] = reinterpret_cast<float *>(static_cast<char *>(ws) + j * vb);
+        g.y[j] = y[j];
+        g.ldy[j] = ldy[j];
+    }
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    rc = do_shrink(pool, layer, g, x, ldx, src_row, seg, st);
+    if (rc != LORA_OK) return rc;
+    return do_expand(pool, layer, g, seg, out_dtype, st);
 }
 
 size_t lora_moe_ws_bytes(const lora_pool *pool, int P)
@@ -714,28 +833,40 @@ int moe_expand_checks(const lora_pool *pool, int which, void *y0, void *y1, int6
     return LORA_OK;
 }
 
+// UPGATE: projections 0 (gate) and 1 (up) sharing the token rows; DOWN: projection 2
+Group moe_group(const lora_pool *pool, int which, const lora_segments *seg, void *ws, void *y0,
+                void *y1, int64_t ldy)
+{
+    Group g;
+    memset(&g, 0, sizeof g);
+    g.v[0] = static_cast<float *>(ws);
+    g.y[0] = y0;
+    g.ldy[0] = ldy;
+    if (which == LORA_MOE_UPGATE) {
+        g.proj0 = 0;
+        g.n = 2;
+        g.v[1] = reinterpret_cast<float *>(static_cast<char *>(ws) + lora_v_bytes(pool, 0, seg->P));
+        g.y[1] = y1;
+        g.ldy[1] = ldy;
+    } else {
+        g.proj0 = 2;
+        g.n = 1;
+    }
+    return g;
+}
+
 int moe_shrink_launch(const lora_pool *pool, int layer, int which, const void *in, int64_t ld_in,
                       const int32_t *token_of_pair, const lora_segments *seg, void *ws,
                       hipStream_t st)
 {
-    float *v0 = static_cast<float *>(ws);
-    if (which == LORA_MOE_UPGATE) {
-        float *v1 = reinterpret_cast<float *>(static_cast<char *>(ws) + lora_v_bytes(pool, 0, seg->P));
-        return do_shrink(pool, layer, 0, 2, in, ld_in, token_of_pair, seg, v0, v1, st);
-    }
-    return do_shrink(pool, layer, 2, 1, in, ld_in, nullptr, seg, v0, nullptr, st);
+    return do_shrink(pool, layer, moe_group(pool, which, seg, ws, nullptr, nullptr, 0), in, ld_in,
+                     which == LORA_MOE_UPGATE ? token_of_pair : nullptr, seg, st);
 }
 
 int moe_expand_launch(const lora_pool *pool, int layer, int which, const lora_segments *seg,
                       void *y0, void *y1, int64_t ldy, void *ws, hipStream_t st)
 {
-    const float *v0 = static_cast<const float *>(ws);
-    if (which == LORA_MOE_UPGATE) {
-        const float *v1 = reinterpret_cast<const float *>(static_cast<const char *>(ws) +
-                                                          lora_v_bytes(pool, 0, seg->P));
-        return do_expand(pool, layer, 0, 2, v0, v1, seg, y0, y1, ldy, LORA_DTYPE_BF16, st);
-    }
-    return do_expand(pool, layer, 2, 1, v0, nullptr, seg, y0, nullptr, ldy, LORA_DTYPE_BF16, st);
+    return do_expand(pool, layer, moe_group(pool, which, seg, ws, y0, y1, ldy), seg, LORA_DTYPE_BF16, st);
 }
 
 }  // namespace

@@ -38,7 +38,8 @@ __global__ __launch_bounds__(256, 2) void expand_kernel(ExpandParams p)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = lane >> 4, i16 = lane & 15;
     const int n_tiles = p.counts[2];
-    const int cgroups = (p.n_chunks + p.waves - 1) / p.waves;       // chunk groups of a row
+    const int n_chunks = p.n_chunks[0], h_out = p.h_out[0];          // equal for all projections here
+    const int cgroups = (n_chunks + p.waves - 1) / p.waves;         // chunk groups of a row
     const int tgroups = (n_tiles + p.tile_group - 1) / p.tile_group;
     const int per_tgroup = p.n_fused * cgroups;
     const int n_items = tgroups * per_tgroup;
@@ -49,9 +50,9 @@ __global__ __launch_bounds__(256, 2) void expand_kernel(ExpandParams p)
         const int pj = rem / cgroups;
         const int cg = rem - pj * cgroups;
         const int chunk = cg * p.waves + wave;
-        const bool chunk_ok = chunk < p.n_chunks;                  // wave-uniform
+        const bool chunk_ok = chunk < n_chunks;                    // wave-uniform
         const int col = chunk * kColChunk + i16 * 8;               // first of this lane's 8 columns
-        const bool col_ok = chunk_ok && col < p.h_out;
+        const bool col_ok = chunk_ok && col < h_out;
         const float *vsrc = p.v[pj];
         char *ybase = static_cast<char *>(p.y[pj]);
 
@@ -74,7 +75,7 @@ __global__ __launch_bounds__(256, 2) void expand_kernel(ExpandParams p)
                     const int r = sub * 16 + g * 4 + i;
                     rok[sub][i] = col_ok && r < t.n_rows;
                     const int dst = p.perm[t.row0 + min(r, t.n_rows - 1)];
-                    yrow[sub][i] = ybase + ((int64_t)dst * p.ldy + (col_ok ? col : 0)) * ESZ;
+                    yrow[sub][i] = ybase + ((int64_t)dst * p.ldy[pj] + (col_ok ? col : 0)) * ESZ;
                 }
 
             // ---- stage scale * sum_parts(v) as hi/lo bf16 planes -------------------------

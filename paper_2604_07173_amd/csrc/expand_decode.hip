@@ -124,7 +124,7 @@ __device__ inline void expand_item(const ExpandParams &p, const lora_tile &t, co
     w.lane = lane;
     w.g = lane >> 4;
     w.i16 = lane & 15;
-    w.h_out = p.h_out;
+    w.h_out = p.h_out[pj];
     w.Bp = unit.B;
     const float scale = unit.scale;
 #pragma unroll
@@ -132,7 +132,7 @@ __device__ inline void expand_item(const ExpandParams &p, const lora_tile &t, co
         const int r = 4 * i + w.g;                       // row of result register i
         w.rok[i] = r < t.n_rows;
         const int dst = p.perm[t.row0 + min(r, t.n_rows - 1)];
-        w.yrow[i] = static_cast<char *>(p.y[pj]) + (int64_t)dst * p.ldy * ESZ;
+        w.yrow[i] = static_cast<char *>(p.y[pj]) + (int64_t)dst * p.ldy[pj] * ESZ;
     }
 
     // v operand: this lane's row slot i16 holds tile row (i16 % 4) * 4 + i16 / 4
@@ -176,16 +176,16 @@ __global__ __launch_bounds__(256, 2) void expand16_kernel(ExpandParams p,
     const int wpb = blockDim.x >> 6;
     const int gw = __builtin_amdgcn_readfirstlane(blockIdx.x * wpb + wave), nw = gridDim.x * wpb;
     const int n_tiles = counts[2];
-    const int per_tile = p.n_fused * p.n_slices;
+    const int per_tile = p.slice0[p.n_fused];                     // wave items of one tile
     const int n_items = n_tiles * per_tile;
-    const int cps = (p.n_chunks + p.n_slices - 1) / p.n_slices;   // chunks per slice
 
     for (int item = gw; item < n_items; item += nw) {
         const int tile_ix = item / per_tile;
         const int rem = item - tile_ix * per_tile;
-        const int pj = rem / p.n_slices;
-        const int slice = rem - pj * p.n_slices;
-        const int c0 = slice * cps, c1 = min(c0 + cps, p.n_chunks);
+        const int pj = (rem >= p.slice0[1] ? 1 : 0) + (p.n_fused > 2 && rem >= p.slice0[2] ? 1 : 0);
+        const int slice = rem - p.slice0[pj];
+        const int cps = (p.n_chunks[pj] + p.n_slices[pj] - 1) / p.n_slices[pj];   // chunks per slice
+        const int c0 = slice * cps, c1 = min(c0 + cps, p.n_chunks[pj]);
         if (c0 >= c1) continue;
         const lora_tile t = tiles[tile_ix];
         const Unit unit = units[(int64_t)t.key * p.n_proj + p.proj0 + pj];

@@ -26,6 +26,7 @@ constexpr int kKBlock = 32;          // K elements per MFMA step (v_mfma_f32_16x
 constexpr int kColChunk = 128;       // output columns one wave owns in expand
 constexpr int kPartKBlocks = 32;     // K-blocks one shrink workgroup reduces (1024 inputs)
 constexpr int kMaxParts = 64;
+constexpr int kMaxFused = 3;         // projections that share an input in one launch (q/k/v, gate/up)
 
 // ---- packed layout sizes ---------------------------------------------------------------
 inline int kunit_of(int rank) { return rank == 8 ? 64 : kKBlock; }   // K values per packed A block
@@ -67,14 +68,14 @@ struct ShrinkParams {
     const Unit *units;       // table rows of the layer
     int n_proj;              // projections per unit (table stride)
     int proj0;               // first projection handled
-    int n_fused;             // 1 or 2 projections sharing x
+    int n_fused;             // 1 .. kMaxFused consecutive projections sharing x (same h_in)
     const uint16_t *x;
     int64_t ldx;
     const int32_t *src_row;  // may be null
     const int32_t *perm;
     const lora_tile *tiles;
     const int32_t *counts;
-    float *v[2];             // per fused projection: [n_parts][P][rank]
+    float *v[kMaxFused];     // per fused projection: [n_parts][P][rank]
     int P;
     int h_in;
     int n_parts;
@@ -89,18 +90,20 @@ struct ExpandParams {
     const Unit *units;
     int n_proj;
     int proj0;
-    int n_fused;
-    const float *v[2];
+    int n_fused;             // 1 .. kMaxFused consecutive projections (their h_out may differ in
+                             // the decode kernel; the general kernel wants them equal)
+    const float *v[kMaxFused];
     int n_parts;
     int P;
     const int32_t *perm;
     const lora_tile *tiles;
     const int32_t *counts;
-    void *y[2];
-    int64_t ldy;
-    int h_out;
-    int n_chunks;            // 128-column chunks
-    int n_slices;            // decode kernel: wave items per (tile, projection)
+    void *y[kMaxFused];
+    int64_t ldy[kMaxFused];
+    int h_out[kMaxFused];
+    int n_chunks[kMaxFused]; // 128-column chunks
+    int n_slices[kMaxFused]; // decode kernel: wave items per (tile, projection)
+    int slice0[kMaxFused + 1];   // decode kernel: first wave item of a projection within a tile
     int tile_group;          // general kernel: consecutive tiles one workgroup walks over
     int waves;               // waves per workgroup
     int out_f32;

@@ -233,7 +233,12 @@ hipError_t launch_rn(const ShrinkParams &p, hipStream_t s)
 template <int R>
 hipError_t launch_r(const ShrinkParams &p, hipStream_t s)
 {
-    return p.n_fused == 2 ? launch_rn<R, 2>(p, s) : launch_rn<R, 1>(p, s);
+    switch (p.n_fused) {
+    case 1: return launch_rn<R, 1>(p, s);
+    case 2: return launch_rn<R, 2>(p, s);
+    case 3: return launch_rn<R, 3>(p, s);
+    default: return hipErrorInvalidValue;
+    }
 }
 
 }  // namespace

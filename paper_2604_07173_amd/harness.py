@@ -76,9 +76,23 @@ class DeviceBatch:
             self.y[k].copy_(to_dev(v, self.y[k].device))
 
 
+def projection_groups(w: W.Workload):
+    """Runs of consecutive projections that read the same input (q/k/v, gate/up): (first, count),
+    at most three per group."""
+    groups, j = [], 0
+    while j < len(w.projs):
+        n = 1
+        while (j + n < len(w.projs) and n < 3 and w.projs[j + n].input == w.projs[j].input
+               and w.projs[j + n].h_in == w.projs[j].h_in):
+            n += 1
+        groups.append((j, n))
+        j += n
+    return groups
+
+
 class LayerRunner:
     """Issues the calls of one layer over a DeviceBatch: build segments, then per projection
-    shrink + expand (dense) or the two MoE applications."""
+    lora_apply_group per run of projections sharing an input (dense) or the two MoE applications."""
 
     def __init__(self, dp: DevicePool, db: DeviceBatch):
         self.dp, self.db = dp, db
@@ -89,7 +103,9 @@ class LayerRunner:
             self.ws = torch.empty(max(L.lora_moe_ws_bytes(dp.pool, P), 256), dtype=torch.uint8,
                                   device=dp.device)
         else:
-            n = max(L.lora_v_bytes(dp.pool, j, P) for j in range(len(w.projs)))
+            self.groups = projection_groups(w)
+            n = max(max(L.lora_group_ws_bytes(dp.pool, j, c, P) for j, c in self.groups),
+                    max(L.lora_v_bytes(dp.pool, j, P) for j in range(len(w.projs))))
             self.v = torch.empty(max(n, 256) // 4, dtype=torch.float32, device=dp.device)
 
     def build_segments(self, stream=None):
@@ -107,12 +123,16 @@ class LayerRunner:
             L.lora_moe_apply(dp.pool, layer, L.LORA_MOE_DOWN, mid, mid.shape[1], None, db.seg,
                              db.y["down"], None, db.y["down"].shape[1], self.ws, stream=stream)
         else:
-            for j, p in enumerate(w.projs):
-                x = db.inputs[p.input]
-                y = db.y[p.name]
-                L.lora_shrink(dp.pool, layer, j, x, x.shape[1], None, db.seg, self.v, stream=stream)
-                L.lora_expand(dp.pool, layer, j, self.v, db.seg, y, y.shape[1], L.LORA_DTYPE_BF16,
-                              stream=stream)
+            for j, c in self.groups:
+                self.apply_group(layer, j, c, stream)
+
+    def apply_group(self, layer: int, j: int, c: int, stream=None):
+        dp, db = self.dp, self.db
+        projs = dp.workload.projs[j:j + c]
+        x = db.inputs[projs[0].input]
+        ys = [db.y[p.name] for p in projs]
+        L.lora_apply_group(dp.pool, layer, j, x, x.shape[1], None, db.seg, ys,
+                           [y.shape[1] for y in ys], self.v, L.LORA_DTYPE_BF16, stream=stream)
 
     def step(self, layer: int, stream=None):
         self.build_segments(stream)

@@ -107,6 +107,62 @@ def test_thousands_of_small_tiles_one_wave_per_tile(rank, h_in):
     check_accumulate(got, res, f"wave per tile r{rank}")
 
 
+@pytest.mark.parametrize("out_f32", [False, True])
+@pytest.mark.parametrize("rank,h_in,h_out,n,tokens", [(8, 200, 328, 5, 70), (16, 2080, 392, 4, 72),
+                                                      (64, 4104, 1160, 6, 40)])
+def test_apply_is_bit_identical_to_shrink_then_expand(rank, h_in, h_out, n, tokens, out_f32):
+    w = dense_workload(rank, h_in, h_out, n=n, tokens=tokens)
+    b = W.make_batch(w, 31, y_mode="normal", no_adapter_frac=0.1, hetero_scale=True)
+    ws = W.make_weights(w, 31, bank_elems=1 << 20)
+    dp, db = DevicePool(ws, b.scale), DeviceBatch(b)
+    run = LayerRunner(dp, db)
+    run.build_segments()
+    x = db.inputs["x"]
+    dt = L.LORA_DTYPE_F32 if out_f32 else L.LORA_DTYPE_BF16
+
+    def fresh_y():
+        if out_f32:
+            return torch.from_numpy(W.bf16_bits_to_f32(b.y_in["p"])).cuda()
+        return to_dev(b.y_in["p"])
+
+    y_ref, y = fresh_y(), fresh_y()
+    L.lora_shrink(dp.pool, 0, 0, x, x.shape[1], None, db.seg, run.v)
+    L.lora_expand(dp.pool, 0, 0, run.v, db.seg, y_ref, y_ref.shape[1], dt)
+    run.v.fill_(float("nan"))
+    L.lora_apply(dp.pool, 0, 0, x, x.shape[1], None, db.seg, y, y.shape[1], run.v, dt)
+    torch.cuda.synchronize()
+    bits = torch.int32 if out_f32 else torch.int16
+    assert torch.equal(y.view(bits), y_ref.view(bits))
+    if not out_f32:
+        check_accumulate(bits_from_dev(y), oracle_projection(b, ws, 0, 0), "apply")
+
+
+@pytest.mark.parametrize("rank", [8, 16, 32, 64])
+@pytest.mark.parametrize("tokens,n", [(70, 5), (2100, 3)])      # decode tiles / long segments
+def test_group_of_three_projections_matches_single_calls(rank, tokens, n):
+    """q/k/v-like group: same input, widths 392 / 136 / 136; bit-identical to per-projection
+    lora_apply calls and within tolerance of the oracle."""
+    projs = (W.Proj("q", 264, 392, "x"), W.Proj("k", 264, 136, "x"), W.Proj("v", 264, 136, "x"))
+    w = W.Workload("t", "dense", n, 1, 1, rank, projs, tokens, "uniform", 0.0)
+    b = W.make_batch(w, 41, y_mode="normal", no_adapter_frac=0.1, hetero_scale=True)
+    ws = W.make_weights(w, 41, bank_elems=1 << 20)
+    dp, db = DevicePool(ws, b.scale), DeviceBatch(b)
+    run = LayerRunner(dp, db)
+    run.build_segments()
+    assert run.groups == [(0, 3)]
+    x = db.inputs["x"]
+    ref = {}
+    for j, p in enumerate(projs):
+        y = to_dev(b.y_in[p.name])
+        L.lora_apply(dp.pool, 0, j, x, x.shape[1], None, db.seg, y, y.shape[1], run.v)
+        ref[p.name] = y
+    run.apply(0)
+    torch.cuda.synchronize()
+    for j, p in enumerate(projs):
+        assert torch.equal(db.y[p.name], ref[p.name]), p.name
+        check_accumulate(bits_from_dev(db.y[p.name]), oracle_projection(b, ws, 0, j), p.name)
+
+
 def test_shrink_output_matches_oracle_v_and_src_row():
     w = dense_workload(16, 2080, 136, n=4, tokens=72)
     b = W.make_batch(w, 16, hetero_scale=True)
