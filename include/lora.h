@@ -186,9 +186,9 @@ int lora_build_segments(const lora_pool *pool, const int32_t *adapter_id,
  * lora_shrink:  v = gather(x) * A.   Row i of the sorted order reads x row
  *   src_row[perm[i]] (src_row NULL: perm[i]) — Sec. 5.2: activations are scattered and
  *   must be gathered.  x: device bf16, row stride ldx elements.
- *   v: device fp32 workspace of lora_v_bytes(pool, proj, P) bytes; it holds per-K-slice
- *   partial sums in sorted-row order and is meant only to be passed to lora_expand with
- *   the same pool, layer, proj and segments.
+ *   v: device workspace of lora_v_bytes(pool, proj, P) bytes; it holds per-K-slice fp32
+ *   partial sums in sorted-row order (and room that lora_expand uses for itself) and is
+ *   meant only to be passed to lora_expand with the same pool, layer, proj and segments.
  * lora_expand:  y[perm[i]] += scale * v_i * B   (Sec. 2.2: the update is added to the base
  *   output; Fig. 7b: final addition of the two outputs).  y: device, row stride ldy
  *   elements, bf16 (read, add in fp32, round to nearest even, write) or fp32.  Rows that
@@ -199,7 +199,7 @@ size_t lora_v_bytes(const lora_pool *pool, int proj, int P);
 int lora_shrink(const lora_pool *pool, int layer, int proj, const void *x, int64_t ldx,
                 const int32_t *src_row, const lora_segments *seg, float *v, void *stream);
 
-int lora_expand(const lora_pool *pool, int layer, int proj, const float *v,
+int lora_expand(const lora_pool *pool, int layer, int proj, float *v,
                 const lora_segments *seg, void *y, int64_t ldy, int out_dtype, void *stream);
 
 /*

@@ -234,6 +234,12 @@ struct Group {
     int64_t ldy[kMaxFused];
 };
 
+// bytes of the K parts of one projection's intermediate
+size_t parts_bytes(const lora_pool *pool, int n_parts, int P)
+{
+    return align_up((size_t)n_parts * std::max(P, 1) * pool->d.rank * sizeof(float), 256);
+}
+
 int do_shrink(const lora_pool *pool, int layer, const Group &g, const void *x, int64_t ldx,
               const int32_t *src_row, const lora_segments *seg, hipStream_t st)
 {
@@ -333,38 +339,29 @@ int do_expand(const lora_pool *pool, int layer, const Group &g, const lora_segme
         LORA_HIP(launch_expand_decode(ep, st));
         return LORA_OK;
     }
-    // general kernel: a workgroup walks over tile_group consecutive tiles with one chunk per
-    // wave held in registers; projections of equal width go two per launch
-    static const int target = env_int("LORA_EXPAND_ITEMS", 1536, 1, 1 << 20);
-    static const int tg_max = env_int("LORA_EXPAND_TILE_GROUP", 1, 1, 1024);
+    // long segments: operand images of the sub-tiles behind the K parts in each projection's
+    // slice of the workspace, then wave items = (group of tiles, projection, 128-column chunk)
     static const int per_cu = env_int("LORA_EXPAND_WGS_PER_CU", 8, 1, 64);
-    for (int j = 0; j < g.n;) {
-        const int h_out = pool->d.proj[g.proj0 + j].h_out;
-        const int nf = (j + 1 < g.n && pool->d.proj[g.proj0 + j + 1].h_out == h_out) ? 2 : 1;
-        ep.proj0 = g.proj0 + j;
-        ep.n_fused = nf;
-        for (int q = 0; q < nf; ++q) {
-            ep.v[q] = g.v[j + q];
-            ep.y[q] = g.y[j + q];
-            ep.ldy[q] = g.ldy[j + q];
-            ep.h_out[q] = h_out;
-            ep.n_chunks[q] = chunks_of(h_out);
-        }
-        const int n_chunks = ep.n_chunks[0];
-        // waves per workgroup: the largest of 4, 3, 2 that divides the chunk count, else 4
-        ep.waves = 4;
-        if (n_chunks % 4 != 0) {
-            if (n_chunks % 3 == 0) ep.waves = 3;
-            else if (n_chunks % 2 == 0) ep.waves = 2;
-            else if (n_chunks < 4) ep.waves = n_chunks;
-        }
-        const int cgroups = (n_chunks + ep.waves - 1) / ep.waves;
-        ep.tile_group = (int)std::max<int64_t>(1, std::min<int64_t>(tg_max, tub * nf * cgroups / target));
-        const int64_t items = ((tub + ep.tile_group - 1) / ep.tile_group) * nf * cgroups;
-        ep.grid = (int)std::min<int64_t>(items, (int64_t)cu_count() * per_cu);
-        LORA_HIP(launch_expand(ep, st));
-        j += nf;
+    ep.proj0 = g.proj0;
+    ep.n_fused = g.n;
+    ep.slice0[0] = 0;
+    for (int j = 0; j < g.n; ++j) {
+        ep.v[j] = g.v[j];
+        ep.y[j] = g.y[j];
+        ep.ldy[j] = g.ldy[j];
+        ep.h_out[j] = pool->d.proj[g.proj0 + j].h_out;
+        ep.n_chunks[j] = chunks_of(ep.h_out[j]);
+        ep.n_slices[j] = ep.n_chunks[j];
+        ep.slice0[j + 1] = ep.slice0[j] + ep.n_chunks[j];
+        ep.img[j] = reinterpret_cast<char *>(g.v[j]) + parts_bytes(pool, ks.n_parts, seg->P);
     }
+    for (int j = g.n; j < kMaxFused; ++j) ep.slice0[j + 1] = ep.slice0[g.n];
+    ep.waves = 4;
+    const int64_t groups = (tub + expand_long_group() - 1) / expand_long_group();
+    const int64_t wave_items = groups * ep.slice0[g.n];
+    ep.grid = (int)std::min<int64_t>((wave_items + 3) / 4, (int64_t)cu_count() * per_cu);
+    ep.image_grid = (int)std::min<int64_t>((tub * 2 * g.n + 3) / 4, (int64_t)cu_count() * 8);
+    LORA_HIP(launch_expand(ep, st));
     return LORA_OK;
 }
 
@@ -673,7 +670,11 @@ size_t lora_v_bytes(const lora_pool *pool, int proj, int P)
 {
     if (check_pool(pool) != LORA_OK || proj < 0 || proj >= pool->d.n_proj || P < 0) return 0;
     const KSplit ks = ksplit_of(pool, proj, P);
-    return align_up((size_t)ks.n_parts * std::max(P, 1) * pool->d.rank * sizeof(float), 256);
+    size_t n = parts_bytes(pool, ks.n_parts, P);
+    // long-segment batches: the expand keeps its operand images behind the K parts
+    if (pick_tile_rows(pool, P) == kTileRows)
+        n += align_up(expand_image_bytes(pool->d.rank, tiles_upper_bound(pool, P, kTileRows)), 256);
+    return n;
 }
 
 int lora_shrink(const lora_pool *pool, int layer, int proj, const void *x, int64_t ldx,
@@ -694,7 +695,7 @@ int lora_shrink(const lora_pool *pool, int layer, int proj, const void *x, int64
                      static_cast<hipStream_t>(stream));
 }
 
-int lora_expand(const lora_pool *pool, int layer, int proj, const float *v,
+int lora_expand(const lora_pool *pool, int layer, int proj, float *v,
                 const lora_segments *seg, void *y, int64_t ldy, int out_dtype, void *stream)
 {
     int rc = check_pool(pool);
@@ -709,7 +710,7 @@ int lora_expand(const lora_pool *pool, int layer, int proj, const float *v,
     if (rc != LORA_OK) return rc;
     if (!v) return LORA_ERR_INVALID_ARG;
     if (!aligned(v, 16)) return LORA_ERR_MISALIGNED;
-    return do_expand(pool, layer, single(proj, const_cast<float *>(v), y, ldy), seg, out_dtype,
+    return do_expand(pool, layer, single(proj, v, y, ldy), seg, out_dtype,
                      static_cast<hipStream_t>(stream));
 }
 

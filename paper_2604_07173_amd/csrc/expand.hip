@@ -3,17 +3,28 @@
 // (App. A.2.2 "expand phase"; Sec. 2.2: the update is added to the base output; Fig. 7b:
 // final addition of the two outputs).
 //
-// Work item = (group of consecutive row tiles, projection, group of 128-column chunks).
-// Every wave of the workgroup owns one chunk of the chunk group and keeps that chunk's packed
-// B in MFMA operand registers for as long as the tiles it walks over belong to the same
-// (adapter, expert): with the long segments of a prefill batch B is read once per tile
-// group instead of once per tile, and the kernel's traffic is the read-modify-write of y.
-// Per tile the workgroup adds the K parts of v in a fixed order, applies the adapter's
-// scale, and stages the result in LDS as two bf16 planes hi + lo (hi = v truncated to bf16,
-// lo = the rounded remainder), so the MFMA sees v to about 16 mantissa bits although its
-// operands are bf16.  The column permutation baked into the packed B leaves each lane with
-// eight consecutive output columns of a row, so the y access is one 16-byte load and one
-// 16-byte store per lane with 16 lanes covering 256 contiguous bytes of a row.
+// With long segments the traffic is the read-modify-write of y; B is small and stays in the
+// L2.  Two launches:
+//
+// 1. operand images: one wave per 16-row sub-tile adds the K parts of v in a fixed order,
+//    applies the adapter's scale and writes the sub-tile's MFMA operand exactly as the lanes
+//    of the second kernel want it: two bf16 planes hi + lo (hi = v truncated to bf16, lo =
+//    the rounded remainder, so the product sees about 16 mantissa bits of v), 64 lanes x 8
+//    or 16 bytes per plane and K step.  This is done once per sub-tile instead of once per
+//    (sub-tile, column chunk).
+//
+// 2. the product: every wave works on its own, no LDS and no barriers.  Work item (per
+//    wave) = (group of kLongGroup consecutive tiles, projection, 128-column chunk).  The
+//    wave keeps the chunk's packed B in MFMA operand registers for as long as the tiles
+//    belong to the same (adapter, expert) and walks over the group's 16-row sub-tiles,
+//    software-pipelined three deep: while sub-tile q is multiplied and written back, the
+//    operand image and the base-output rows of sub-tile q+1 are in flight, and the row
+//    indices of sub-tile q+2 are being fetched.  All loads are unconditional (rows beyond a
+//    tile re-read a valid row and are not stored), so the code is straight-line.
+//
+// Row placement as in the decode kernel: tile row r of a sub-tile sits in MFMA row slot
+// (r % 4) * 4 + r / 4, so result register i of lane group g is row 4*i + g and each y
+// access of a wave covers four rows x 256 contiguous bytes.
 #include <type_traits>
 
 #include "expand_common.h"
@@ -23,149 +34,210 @@ namespace lora {
 
 namespace {
 
-template <int R, bool F32>
-__global__ __launch_bounds__(256, 2) void expand_kernel(ExpandParams p)
+constexpr int kLongGroup = 4;        // tiles one wave item walks over (128 rows)
+
+// vec elements of one sub-tile's operand image
+template <int R>
+__host__ __device__ constexpr int image_vecs()
+{
+    return ExpandTile<R>::KS * 2 * 64;
+}
+
+template <int R>
+__global__ __launch_bounds__(256) void operand_image_kernel(ExpandParams p,
+                                                            const lora_tile *__restrict__ tiles,
+                                                            const Unit *__restrict__ units,
+                                                            const int32_t *__restrict__ counts)
 {
     using Tile = ExpandTile<R>;
-    constexpr int KS = Tile::KS;                  // MFMA K steps over the rank
-    constexpr int TR = kTileRows;
-    constexpr int SUB = TR / 16;
-    constexpr int LD = R + 8;                     // padded LDS row (bf16 elements)
-    constexpr int ESZ = F32 ? 4 : 2;
-    __shared__ __attribute__((aligned(16))) uint16_t v_hi[TR][LD];
-    __shared__ __attribute__((aligned(16))) uint16_t v_lo[TR][LD];
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    typedef typename Tile::vec vec;
+    constexpr int KS = Tile::KS, KV = Tile::KV;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int g = lane >> 4, i16 = lane & 15;
-    const int n_tiles = p.counts[2];
-    const int n_chunks = p.n_chunks[0], h_out = p.h_out[0];          // equal for all projections here
-    const int cgroups = (n_chunks + p.waves - 1) / p.waves;         // chunk groups of a row
-    const int tgroups = (n_tiles + p.tile_group - 1) / p.tile_group;
-    const int per_tgroup = p.n_fused * cgroups;
-    const int n_items = tgroups * per_tgroup;
+    const int gw = __builtin_amdgcn_readfirstlane(blockIdx.x * 4 + wave), nw = gridDim.x * 4;
+    const int n_slots = counts[2] * 2;                 // 16-row sub-tiles, two per tile
+    const int64_t part_stride = (int64_t)p.P * R;
 
-    for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
-        const int tg = item / per_tgroup;
-        const int rem = item - tg * per_tgroup;
-        const int pj = rem / cgroups;
-        const int cg = rem - pj * cgroups;
-        const int chunk = cg * p.waves + wave;
-        const bool chunk_ok = chunk < n_chunks;                    // wave-uniform
-        const int col = chunk * kColChunk + i16 * 8;               // first of this lane's 8 columns
-        const bool col_ok = chunk_ok && col < h_out;
-        const float *vsrc = p.v[pj];
-        char *ybase = static_cast<char *>(p.y[pj]);
-
-        typename Tile::B b;
-        int b_key = -1;                                            // key whose B is in registers
-
-        const int t_end = min((tg + 1) * p.tile_group, n_tiles);
-        for (int ti = tg * p.tile_group; ti < t_end; ++ti) {
-            const lora_tile t = p.tiles[ti];
-            const Unit unit = p.units[(int64_t)t.key * p.n_proj + p.proj0 + pj];
-
-            // destination rows of this lane (issued before the staging so that their latency
-            // overlaps with it)
-            char *yrow[SUB][4];
-            bool rok[SUB][4];
+    for (int s = gw; s < n_slots * p.n_fused; s += nw) {
+        const int pj = s / n_slots;
+        const int slot = s - pj * n_slots;
+        const lora_tile t = tiles[slot >> 1];
+        const float scale = units[(int64_t)t.key * p.n_proj + p.proj0 + pj].scale;
+        const int row = (slot & 1) * 16 + (i16 & 3) * 4 + (i16 >> 2);
+        const bool valid = row < t.n_rows;
+        const float *vrow = p.v[pj] + (int64_t)(t.row0 + (valid ? row : 0)) * R;
+        LORA_GLOBAL vec *img = (LORA_GLOBAL vec *)p.img[pj] + (int64_t)slot * image_vecs<R>();
+        typename Tile::A a;
 #pragma unroll
-            for (int sub = 0; sub < SUB; ++sub)
+        for (int ks = 0; ks < KS; ++ks) {
+            const int jb = Tile::jbase(g, ks);
+            float sum[KV];
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int r = sub * 16 + g * 4 + i;
-                    rok[sub][i] = col_ok && r < t.n_rows;
-                    const int dst = p.perm[t.row0 + min(r, t.n_rows - 1)];
-                    yrow[sub][i] = ybase + ((int64_t)dst * p.ldy[pj] + (col_ok ? col : 0)) * ESZ;
+            for (int q = 0; q < KV; ++q) sum[q] = 0.f;
+            for (int part = 0; part < p.n_parts; ++part) {
+#pragma unroll
+                for (int h = 0; h < KV / 4; ++h) {
+                    const f32x4 x = ld16f(vrow + part * part_stride + jb + 4 * h);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) sum[4 * h + q] += x[q];
                 }
+            }
+#pragma unroll
+            for (int q = 0; q < KV; ++q) sum[q] = valid ? sum[q] * scale : 0.f;
+            Tile::make_a(sum, g, ks, a);
+            img[(ks * 2 + 0) * 64 + lane] = a.hi[ks];
+            img[(ks * 2 + 1) * 64 + lane] = a.lo[ks];
+        }
+    }
+}
 
-            // ---- stage scale * sum_parts(v) as hi/lo bf16 planes -------------------------
-            for (int o = tid; o < TR * (R / 4); o += blockDim.x) {
-                const int row = o / (R / 4);
-                const int j = (o - row * (R / 4)) * 4;
-                f32x4 s = {0.f, 0.f, 0.f, 0.f};
-                if (row < t.n_rows) {
-                    const float *src = vsrc + ((int64_t)(t.row0 + row)) * R + j;
-                    for (int part = 0; part < p.n_parts; ++part)
-                        s += ld16f(src + (int64_t)part * p.P * R);
-                    s *= unit.scale;
-                }
-                unsigned hi[4];
-                float lo[4];
+template <int R, bool F32>
+struct LongWave {
+    using Tile = ExpandTile<R>;
+    typedef typename Tile::vec vec;
+    static constexpr int KS = Tile::KS;
+    static constexpr int NY = F32 ? 2 : 1;
+    static constexpr int ESZ = F32 ? 4 : 2;
+    static constexpr int NSLOT = 2 * kLongGroup;
+
+    struct Rows {                 // stage 1: where the sub-tile's rows live
+        char *y[4];
+        bool ok[4];
+    };
+    struct Data {                 // stage 2: the sub-tile's operand and base output
+        typename Tile::A a;
+        u32x4 y[4][NY];
+    };
+
+    int lane, g, i16;
+    const int32_t *perm;
+    char *ybase;                  // y + this lane's first column
+    int64_t ld_bytes;
+    bool col_ok;
+    const LORA_GLOBAL vec *img;
+    lora_tile tl[kLongGroup];
+    int tix[kLongGroup];
+    bool live[kLongGroup];
+
+    __device__ inline void rows_of(int q, Rows &r) const
+    {
+        const int k = q >> 1, sub = q & 1;
+        const int n = live[k] ? tl[k].n_rows : 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int row = sub * 16 + 4 * i + g;
+            r.ok[i] = col_ok && row < n;
+            const int dst = perm[tl[k].row0 + min(row, tl[k].n_rows - 1)];
+            r.y[i] = ybase + (int64_t)dst * ld_bytes;
+        }
+    }
+
+    __device__ inline void load(int q, const Rows &r, Data &d) const
+    {
+        const int k = q >> 1, sub = q & 1;
+        const LORA_GLOBAL vec *im = img + (int64_t)(tix[k] * 2 + sub) * image_vecs<R>();
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            d.a.hi[ks] = im[(ks * 2 + 0) * 64 + lane];
+            d.a.lo[ks] = im[(ks * 2 + 1) * 64 + lane];
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int h = 0; h < NY; ++h) d.y[i][h] = ld16<false>(r.y[i] + 16 * h);
+    }
+
+    __device__ inline void compute_store(const Rows &r, const Data &d, const typename Tile::B &b) const
+    {
+        f32x4 acc[8];
+        Tile::mma(d.a, b, acc);
+        // the sums are formed for every lane; only the store itself is predicated
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if (F32) {
+                u32x4 o0, o1;
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    const unsigned u = __float_as_uint(s[q]) & 0xFFFF0000u;
-                    hi[q] = u >> 16;
-                    lo[q] = s[q] - __uint_as_float(u);
+                    o0[q] = __float_as_uint(__uint_as_float(d.y[i][0][q]) + acc[q][i]);
+                    o1[q] = __float_as_uint(__uint_as_float(d.y[i][NY - 1][q]) + acc[4 + q][i]);
                 }
-                *reinterpret_cast<u32x2 *>(&v_hi[row][j]) =
-                    u32x2{hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16)};
-                *reinterpret_cast<u32x2 *>(&v_lo[row][j]) =
-                    u32x2{pack_bf16_rne(lo[0], lo[1]), pack_bf16_rne(lo[2], lo[3])};
+                if (r.ok[i]) {
+                    st16<false>(r.y[i], o0);
+                    st16<false>(r.y[i] + 16, o1);
+                }
+            } else {
+                u32x4 o;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const unsigned u = d.y[i][0][q];
+                    const float f0 = __uint_as_float(u << 16) + acc[2 * q][i];
+                    const float f1 = __uint_as_float(u & 0xFFFF0000u) + acc[2 * q + 1][i];
+                    o[q] = pack_bf16_rne(f0, f1);
+                }
+                if (r.ok[i]) st16<false>(r.y[i], o);
             }
-            __syncthreads();
+        }
+    }
+};
 
-            if (chunk_ok) {
-                if (t.key != b_key) {                              // wave-uniform
-                    Tile::template load_b<false>(unit.B, chunk, lane, b);
-                    b_key = t.key;
-                }
-                // base output of both sub-tiles first, so that all of the tile's y is in flight
-                // at once: MFMA result register i of sub-tile s holds row 16*s + 4*g + i; rows
-                // beyond the tile read the tile's first row and are not stored
-                u32x4 yv[SUB][4][F32 ? 2 : 1];
-#pragma unroll
-                for (int sub = 0; sub < SUB; ++sub)
-#pragma unroll
-                    for (int i = 0; i < 4; ++i)
-#pragma unroll
-                        for (int q = 0; q < (F32 ? 2 : 1); ++q) yv[sub][i][q] = ld16<false>(yrow[sub][i] + 16 * q);
+template <int R, bool F32>
+__global__ __launch_bounds__(256, 2) void expand_long_kernel(ExpandParams p,
+                                                             const lora_tile *__restrict__ tiles,
+                                                             const Unit *__restrict__ units,
+                                                             const int32_t *__restrict__ counts)
+{
+    using Wave = LongWave<R, F32>;
+    using Tile = ExpandTile<R>;
+    constexpr int NSLOT = Wave::NSLOT;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int gw = __builtin_amdgcn_readfirstlane(blockIdx.x * 4 + wave), nw = gridDim.x * 4;
+    const int n_tiles = counts[2];
+    const int n_groups = (n_tiles + kLongGroup - 1) / kLongGroup;
+    const int per_group = p.slice0[p.n_fused];                    // chunks of all projections
+    const int n_items = n_groups * per_group;
 
-#pragma unroll
-                for (int sub = 0; sub < SUB; ++sub) {
-                    // v operand of the sub-tile: row i16, this lane group's K values
-                    const int row = sub * 16 + i16;
-                    typename Tile::A a;
-#pragma unroll
-                    for (int ks = 0; ks < KS; ++ks) {
-                        const int jb = Tile::jbase(g, ks);
-                        typedef typename Tile::vec vec;
-                        const vec vh = *reinterpret_cast<const vec *>(&v_hi[row][jb]);
-                        const vec vl = *reinterpret_cast<const vec *>(&v_lo[row][jb]);
-                        a.hi[ks] = (R == 8 && g >= 2) ? vl : vh;
-                        a.lo[ks] = vl;
-                    }
-                    f32x4 acc[8];
-                    Tile::mma(a, b, acc);
+    for (int item = gw; item < n_items; item += nw) {
+        const int tg = item / per_group;
+        const int rem = item - tg * per_group;
+        const int pj = (rem >= p.slice0[1] ? 1 : 0) + (p.n_fused > 2 && rem >= p.slice0[2] ? 1 : 0);
+        const int chunk = rem - p.slice0[pj];
 
-                    // y += delta: lane owns columns col .. col+7 of rows 4*g + i
+        Wave w;
+        w.lane = lane;
+        w.g = lane >> 4;
+        w.i16 = lane & 15;
+        w.perm = p.perm;
+        const int col = chunk * kColChunk + w.i16 * 8;
+        w.col_ok = col < p.h_out[pj];
+        w.ybase = static_cast<char *>(p.y[pj]) + (int64_t)(w.col_ok ? col : 0) * Wave::ESZ;
+        w.ld_bytes = p.ldy[pj] * Wave::ESZ;
+        w.img = (const LORA_GLOBAL typename Wave::vec *)p.img[pj];
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        if (F32) {
-                            u32x4 o0, o1;
+        for (int k = 0; k < kLongGroup; ++k) {
+            w.live[k] = tg * kLongGroup + k < n_tiles;
+            w.tix[k] = min(tg * kLongGroup + k, n_tiles - 1);
+            w.tl[k] = tiles[w.tix[k]];
+        }
+
+        typename Tile::B b;
+        int b_key = w.tl[0].key;
+        Tile::template load_b<false>(units[(int64_t)b_key * p.n_proj + p.proj0 + pj].B, chunk, lane, b);
+
+        typename Wave::Rows rows[3];
+        typename Wave::Data data[2];
+        w.rows_of(0, rows[0]);
+        w.rows_of(1, rows[1]);
+        w.load(0, rows[0], data[0]);
 #pragma unroll
-                            for (int q = 0; q < 4; ++q) {
-                                o0[q] = __float_as_uint(__uint_as_float(yv[sub][i][0][q]) + acc[q][i]);
-                                o1[q] = __float_as_uint(__uint_as_float(yv[sub][i][F32 ? 1 : 0][q]) + acc[4 + q][i]);
-                            }
-                            if (rok[sub][i]) {
-                                st16<false>(yrow[sub][i], o0);
-                                st16<false>(yrow[sub][i] + 16, o1);
-                            }
-                        } else {
-                            u32x4 o;
-#pragma unroll
-                            for (int q = 0; q < 4; ++q) {
-                                const unsigned u = yv[sub][i][0][q];
-                                const float f0 = __uint_as_float(u << 16) + acc[2 * q][i];
-                                const float f1 = __uint_as_float(u & 0xFFFF0000u) + acc[2 * q + 1][i];
-                                o[q] = pack_bf16_rne(f0, f1);
-                            }
-                            if (rok[sub][i]) st16<false>(yrow[sub][i], o);
-                        }
-                    }
-                }
+        for (int q = 0; q < NSLOT; ++q) {
+            if (q + 2 < NSLOT) w.rows_of(q + 2, rows[(q + 2) % 3]);
+            if (q + 1 < NSLOT) w.load(q + 1, rows[(q + 1) % 3], data[(q + 1) & 1]);
+            const int key = w.tl[q >> 1].key;
+            if (key != b_key) {                                   // wave-uniform, rare
+                b_key = key;
+                Tile::template load_b<false>(units[(int64_t)key * p.n_proj + p.proj0 + pj].B, chunk, lane, b);
             }
-            __syncthreads();
+            w.compute_store(rows[q % 3], data[q & 1], b);
         }
     }
 }
@@ -173,22 +245,35 @@ __global__ __launch_bounds__(256, 2) void expand_kernel(ExpandParams p)
 template <int R>
 hipError_t launch_r(const ExpandParams &p, hipStream_t s)
 {
-    const dim3 block(p.waves * 64);
+    hipLaunchKernelGGL((operand_image_kernel<R>), dim3(p.image_grid), dim3(256), 0, s, p, p.tiles,
+                       p.units, p.counts);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
     if (p.out_f32)
-        hipLaunchKernelGGL((expand_kernel<R, true>), dim3(p.grid), block, 0, s, p);
+        hipLaunchKernelGGL((expand_long_kernel<R, true>), dim3(p.grid), dim3(256), 0, s, p, p.tiles,
+                           p.units, p.counts);
     else
-        hipLaunchKernelGGL((expand_kernel<R, false>), dim3(p.grid), block, 0, s, p);
+        hipLaunchKernelGGL((expand_long_kernel<R, false>), dim3(p.grid), dim3(256), 0, s, p, p.tiles,
+                           p.units, p.counts);
     return hipGetLastError();
 }
 
 }  // namespace
 
+size_t expand_image_bytes(int rank, int64_t n_tiles)
+{
+    const int ks = rank >= 32 ? rank / 32 : 1;
+    const size_t vec_bytes = rank <= 16 ? 8 : 16;
+    return (size_t)n_tiles * 2 * ks * 2 * 64 * vec_bytes;
+}
+
+int expand_long_group() { return kLongGroup; }
+
 hipError_t launch_expand(const ExpandParams &p, hipStream_t s)
 {
     if (p.grid <= 0) return hipSuccess;
     switch (p.rank) {
-    case 8: return launch_r<8>(p, s);
-    case 16: return launch_r<16>(p, s);
+    case 16: return launch_r<16>(p, s);       // rank 8 always runs with 16-row tiles
     case 32: return launch_r<32>(p, s);
     case 64: return launch_r<64>(p, s);
     default: return hipErrorInvalidValue;

@@ -104,7 +104,8 @@ struct ExpandParams {
     int n_chunks[kMaxFused]; // 128-column chunks
     int n_slices[kMaxFused]; // decode kernel: wave items per (tile, projection)
     int slice0[kMaxFused + 1];   // decode kernel: first wave item of a projection within a tile
-    int tile_group;          // general kernel: consecutive tiles one workgroup walks over
+    void *img[kMaxFused];    // long-segment kernel: operand images of the 16-row sub-tiles
+    int image_grid;          // long-segment kernel: workgroups of the image launch
     int waves;               // waves per workgroup
     int out_f32;
     int rank;
@@ -119,6 +120,8 @@ hipError_t launch_unpack_B(const PackParams &p, hipStream_t s);
 hipError_t launch_segments(const SegParams &p, hipStream_t s);
 hipError_t launch_shrink(const ShrinkParams &p, hipStream_t s);
 hipError_t launch_expand(const ExpandParams &p, hipStream_t s);
+size_t expand_image_bytes(int rank, int64_t n_tiles);   // operand images of n_tiles 32-row tiles
+int expand_long_group();                                 // tiles per wave item of launch_expand
 hipError_t launch_shrink_decode(const ShrinkParams &p, hipStream_t s);   // tiles of <= 16 rows
 hipError_t launch_expand_decode(const ExpandParams &p, hipStream_t s);
 
