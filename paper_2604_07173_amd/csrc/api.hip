@@ -653,9 +653,10 @@ int lora_build_segments(const lora_pool *pool, const int32_t *adapter_id, const 
     sp.n_experts = pool->d.n_experts;
     sp.tile_rows = seg->tile_rows;
     const uint32_t n_keys = (uint32_t)pool->d.n_adapters * (uint32_t)pool->d.n_experts;
-    int bits = 0;
-    while ((n_keys >> bits) != 0) ++bits;      // the sentinel key n_keys must be representable
-    sp.passes = std::max(1, (bits + 7) / 8);
+    int bits = 1;
+    while (((n_keys - 1) >> bits) != 0) ++bits;    // bits of the largest key
+    sp.key_bits = bits;
+    sp.passes = (bits + 7) / 8;
     sp.perm = seg->perm;
     sp.seg_start = seg->seg_start;
     sp.seg_key = seg->seg_key;

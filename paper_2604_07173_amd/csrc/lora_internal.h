@@ -56,6 +56,7 @@ struct SegParams {
     int n_experts;
     int tile_rows;
     int passes;              // radix passes of 8 bits over the key
+    int key_bits;            // bits of the largest key
     int32_t *perm;
     int32_t *seg_start;
     int32_t *seg_key;

@@ -114,17 +114,17 @@ __device__ inline void block_scan3(int cnt, int last, int first, ScanLds *s,
 }
 
 // Lanes of the wave whose digit equals mine (restricted to valid lanes), as two 32-bit
-// halves.  Per key bit: one ballot, then keep the lanes whose bit equals mine.
+// halves.  Per digit bit that can be set: one ballot, then keep the lanes whose bit equals mine.
 struct Match {
     unsigned lo, hi;
 };
 
-__device__ __noinline__ Match match_digit(unsigned digit, bool valid)
+__device__ __noinline__ Match match_digit(unsigned digit, bool valid, int nbits)
 {
     const unsigned long long v = __ballot(valid);
     Match m = {(unsigned)v, (unsigned)(v >> 32)};
 #pragma unroll 1
-    for (int b = 0; b < 8; ++b) {
+    for (int b = 0; b < nbits; ++b) {
         const unsigned bit = (digit >> b) & 1u;
         const unsigned long long bal = __ballot(valid && bit);
         const unsigned same = 0u - bit;                  // all ones if my bit is set
@@ -154,10 +154,11 @@ __global__ __launch_bounds__(kThreads) void segments_kernel(SegParams p)
     unsigned *key_of = reinterpret_cast<unsigned *>(dyn_lds);                    // [P_pad]
     uint16_t *order[2] = {reinterpret_cast<uint16_t *>(key_of + P_pad),          // [P_pad] each
                           reinterpret_cast<uint16_t *>(key_of + P_pad) + P_pad};
-    const unsigned n_keys = (unsigned)p.n_adapters * (unsigned)p.n_experts;      // sentinel key
+    const unsigned n_keys = (unsigned)p.n_adapters * (unsigned)p.n_experts;
+    constexpr unsigned kNoKey = 0xFFFFFFFFu;               // row without adapter: dropped by pass 0
     const int items = (P + kThreads - 1) / kThreads;       // 64-row groups per wave
     const int wave_base = w * items * 64;
-    const bool park = n_keys < 0xFFFFu;                    // room for a 16-bit rank above the key
+    const bool park = n_keys <= 0x10000u;                  // room for a 16-bit rank above the key
     const unsigned key_mask = park ? 0xFFFFu : 0xFFFFFFFFu;
 
     if (tid == 0) {
@@ -179,7 +180,7 @@ __global__ __launch_bounds__(kThreads) void segments_kernel(SegParams p)
             const bool e_ok = e >= 0 && e < p.n_experts;
             const bool none = a == -1;
             const bool ok = a_ok && e_ok;
-            key_of[i] = ok ? (unsigned)a * (unsigned)p.n_experts + (unsigned)e : n_keys;
+            key_of[i] = ok ? (unsigned)a * (unsigned)p.n_experts + (unsigned)e : kNoKey;
             n_active += ok ? 1 : 0;
             if (!none && !ok)
                 bad |= (a_ok ? 0u : (unsigned)LORA_STATUS_BAD_ADAPTER) |
@@ -196,7 +197,9 @@ __global__ __launch_bounds__(kThreads) void segments_kernel(SegParams p)
     // ---- radix passes over the row order ----------------------------------------------
     for (int pass = 0; pass < p.passes; ++pass) {
         const int shift = 8 * pass;
+        const int nbits = min(8, p.key_bits - shift);      // digit bits that can be set
         const bool last = pass == p.passes - 1;
+        const int n_in = pass == 0 ? P : P_act;            // pass 0 leaves the rows without adapter out
         const uint16_t *src = order[(pass + 1) & 1];   // unused in pass 0 (identity order)
         uint16_t *dst = order[pass & 1];
         unsigned *my_hist = hist[w];
@@ -206,11 +209,13 @@ __global__ __launch_bounds__(kThreads) void segments_kernel(SegParams p)
 #pragma unroll 1
         for (int g = 0; g < items; ++g) {
             const int i = wave_base + g * 64 + lane;
-            const bool val = i < P;
-            const unsigned row = val ? (pass == 0 ? (unsigned)i : (unsigned)src[i]) : 0u;
-            const unsigned k = val ? key_of[row] & key_mask : 0u;
+            const bool in = i < n_in;
+            const unsigned row = in ? (pass == 0 ? (unsigned)i : (unsigned)src[i]) : 0u;
+            const unsigned kfull = in ? key_of[row] : kNoKey;
+            const bool val = in && (pass != 0 || kfull != kNoKey);
+            const unsigned k = val ? kfull & key_mask : 0u;
             const unsigned dig = (k >> shift) & 255u;
-            const Match m = match_digit(dig, val);
+            const Match m = match_digit(dig, val, nbits);
             const unsigned below = lanes_below(m);
             // every lane reads the digit's running count before the leader advances it; LDS
             // operations of one wave execute in program order
@@ -239,15 +244,17 @@ __global__ __launch_bounds__(kThreads) void segments_kernel(SegParams p)
 #pragma unroll 1
         for (int g = 0; g < items; ++g) {
             const int i = wave_base + g * 64 + lane;
-            const bool val = i < P;
-            const unsigned row = val ? (pass == 0 ? (unsigned)i : (unsigned)src[i]) : 0u;
-            const unsigned kw = val ? key_of[row] : 0u;
+            const bool in = i < n_in;
+            const unsigned row = in ? (pass == 0 ? (unsigned)i : (unsigned)src[i]) : 0u;
+            const unsigned kfull = in ? key_of[row] : kNoKey;
+            const bool val = in && (pass != 0 || kfull != kNoKey);
+            const unsigned kw = val ? kfull : 0u;
             const unsigned dig = ((kw & key_mask) >> shift) & 255u;
             unsigned pos;
             if (park) {
                 pos = my_hist[dig] + (kw >> 16);
             } else {
-                const Match m = match_digit(dig, val);
+                const Match m = match_digit(dig, val, nbits);
                 const unsigned below = lanes_below(m);
                 const unsigned first = *(volatile unsigned *)&my_hist[dig];
                 pos = first + below;
