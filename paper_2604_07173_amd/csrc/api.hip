@@ -199,9 +199,11 @@ KSplit ksplit_of(const lora_pool *p, int proj, int P)
         k.wave_per_tile = false;
         return k;
     }
+    // long segments: work items are groups of tiles; enough K parts to fill the chip
     const int64_t tub = std::max<int64_t>(1, tiles_upper_bound(p, P, kTileRows));
-    static const int target = env_int("LORA_SHRINK_ITEMS", 1024, 1, 1 << 20);
-    int want = (int)std::min<int64_t>((target + tub - 1) / tub, kMaxParts);
+    const int64_t groups = (tub + shrink_long_tiles() - 1) / shrink_long_tiles();
+    static const int target = env_int("LORA_SHRINK_ITEMS", 512, 1, 1 << 20);
+    int want = (int)std::min<int64_t>((target + groups - 1) / groups, kMaxParts);
     int by_size = (kblocks + kPartKBlocks - 1) / kPartKBlocks;
     int n = std::max(want, by_size);
     n = std::min(n, std::max(1, kblocks / 4));
@@ -274,9 +276,11 @@ int do_shrink(const lora_pool *pool, int layer, const Group &g, const void *x, i
         LORA_HIP(launch_shrink_decode(sp, st));
         return LORA_OK;
     }
-    // 32-row tiles: at most two projections per launch
-    static const int per_cu = env_int("LORA_SHRINK_WGS_PER_CU", 4, 1, 64);
-    sp.grid = (int)std::min<int64_t>(items, (int64_t)cu_count() * per_cu);
+    // 32-row tiles: work items are groups of tiles; at most two projections per launch
+    static const int per_cu = env_int("LORA_SHRINK_WGS_PER_CU", 2, 1, 64);
+    const int64_t groups = (tiles_upper_bound(pool, seg->P, seg->tile_rows) + shrink_long_tiles() - 1) /
+                           shrink_long_tiles();
+    sp.grid = (int)std::min<int64_t>(groups * ks.n_parts, (int64_t)cu_count() * per_cu);
     for (int j = 0; j < g.n; j += 2) {
         sp.proj0 = g.proj0 + j;
         sp.n_fused = std::min(2, g.n - j);

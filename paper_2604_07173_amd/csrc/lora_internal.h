@@ -120,6 +120,7 @@ hipError_t launch_unpack_A(const PackParams &p, hipStream_t s);   // src = packe
 hipError_t launch_unpack_B(const PackParams &p, hipStream_t s);
 hipError_t launch_segments(const SegParams &p, hipStream_t s);
 hipError_t launch_shrink(const ShrinkParams &p, hipStream_t s);
+int shrink_long_tiles();                                 // tiles per work item of launch_shrink
 hipError_t launch_expand(const ExpandParams &p, hipStream_t s);
 size_t expand_image_bytes(int rank, int64_t n_tiles);   // operand images of n_tiles 32-row tiles
 int expand_long_group();                                 // tiles per wave item of launch_expand

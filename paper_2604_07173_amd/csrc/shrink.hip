@@ -1,18 +1,23 @@
-// Shrink: v = gather(x) * A for every row tile (App. A.2.2 "shrink phase"; Sec. 2.2 x A).
+// Shrink for batches with long segments (tiles of up to 32 rows): v = gather(x) * A
+// (App. A.2.2 "shrink phase"; Sec. 2.2 x A).
 //
-// Work item = (row tile of one segment, K part).  A workgroup of four waves takes one item;
-// each wave owns a quarter of the part's K range, streams that slice of the packed A once
-// (one 16-byte load per lane = one contiguous 1 KiB per wave) straight into MFMA operand
-// registers and multiplies it with up to 32 gathered x rows.  The rank index sits on the M
-// side of v_mfma_f32_16x16x32_bf16 and the rows on the N side, so a lane ends up with four
-// consecutive rank entries of one row.  The four waves' partial sums are added through LDS
-// in a fixed order and stored as this part's slice of v; lora_expand adds the parts, again
-// in a fixed order, so results are bit-identical run to run.
+// With long segments the traffic is the read of x; A is small, but a wave that multiplies it
+// with only 32 rows re-reads it from the L2 four times as fast as x arrives from HBM.  So the
+// four waves of a workgroup take four consecutive tiles (up to 128 rows) and share A through
+// LDS: work item = (group of four tiles, K part).  Per stage of four K blocks the workgroup
+// copies the packed A blocks of the first tile's (adapter, expert) into one of two LDS
+// buffers while the previous stage is being multiplied; every wave gathers the x rows of its
+// own tile (the next stage's rows are in flight during the current stage's MFMAs) and reads
+// its MFMA operands from LDS with 16-byte reads that are contiguous per wave.  A group whose
+// tiles do not all belong to one (adapter, expert) (a segment boundary inside the group) takes
+// a plain path in which every wave reads its own A from global memory.  Every wave owns its rows for the
+// whole K part, so there is no cross-wave reduction; lora_expand adds the K parts in a fixed
+// order, so results are bit-identical run to run.
 //
+// The rank index sits on the M side of v_mfma_f32_16x16x32_bf16 and the rows on the N side, so
+// a lane ends up with four consecutive rank entries of one row.  With two fused projections
+// (gate and up, or two projections of a group that read the same input) x is loaded once.
 // Ranks 16, 32 and 64; rank-8 pools always use the 16-row-tile kernels.
-//
-// With two fused projections (the MoE gate and up matrices) the gathered x operand is
-// loaded once and used for both.
 #include "lora_device.h"
 #include "lora_internal.h"
 
@@ -20,51 +25,68 @@ namespace lora {
 
 namespace {
 
+constexpr int kLongTiles = 4;        // tiles (waves) per work item
+constexpr int kStageKB = 4;          // K blocks per LDS stage
+
 template <int R, int NPROJ>
-__global__ __launch_bounds__(256, 2) void shrink_kernel(ShrinkParams p)
+__global__ __launch_bounds__(256, 2) void shrink_long_kernel(ShrinkParams p,
+                                                             const lora_tile *__restrict__ tiles,
+                                                             const Unit *__restrict__ units,
+                                                             const int32_t *__restrict__ counts)
 {
-    constexpr int NB = R / 16;                            // 16-wide blocks of the rank index
-    constexpr int KB = R == 16 ? 8 : (R == 32 ? 4 : 2);   // K blocks loaded per step
-    constexpr int SUB = kTileRows / 16;                   // 16-row sub-tiles per tile
-    __shared__ f32x4 red[4][NPROJ][SUB][NB][64];
+    constexpr int NB = R / 16;                         // 16-wide blocks of the rank index
+    constexpr int BLK = NPROJ * NB;                    // 1 KiB operand blocks per K block
+    constexpr int STAGE = kStageKB * BLK * 64;         // 16-byte vectors per stage
+    constexpr int LOADS = STAGE / 256;                 // per thread and stage
+    constexpr int SUB = kTileRows / 16;
+    static_assert(STAGE % 256 == 0, "a stage is copied by whole workgroup passes");
+    __shared__ u32x4 lds[2][STAGE];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = lane >> 4, i16 = lane & 15;
-    const int n_tiles = p.counts[2];
-    const int n_items = n_tiles * p.n_parts;
+    const int n_tiles = counts[2];
+    const int n_groups = (n_tiles + kLongTiles - 1) / kLongTiles;
+    const int n_items = n_groups * p.n_parts;
     const int kblocks = (p.h_in + kKBlock - 1) / kKBlock;
-    const int kb_per_wave = (p.kb_per_part + 3) >> 2;
     const u32x4 zero4 = {0u, 0u, 0u, 0u};
 
     for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
-        const int tile_ix = item / p.n_parts;
-        const int part = item - tile_ix * p.n_parts;
-        const lora_tile t = p.tiles[tile_ix];
-        const int nsub = (t.n_rows + 15) >> 4;
-
-        const uint16_t *Ap[NPROJ];
+        const int grp = item / p.n_parts;
+        const int part = item - grp * p.n_parts;
+        const int key0 = tiles[grp * kLongTiles].key;
+        const int tix = __builtin_amdgcn_readfirstlane(grp * kLongTiles + wave);
+        const bool live = tix < n_tiles;                      // wave-uniform
+        const lora_tile t = tiles[min(tix, n_tiles - 1)];
+        // does every tile of the group belong to the first tile's (adapter, expert)?  Uniform
+        // over the workgroup: every wave looks at all four records.
+        bool same_key = true;
 #pragma unroll
-        for (int pj = 0; pj < NPROJ; ++pj)
-            Ap[pj] = p.units[(int64_t)t.key * p.n_proj + p.proj0 + pj].A;
+        for (int k = 1; k < kLongTiles; ++k)
+            same_key = same_key && tiles[min(grp * kLongTiles + k, n_tiles - 1)].key == key0;
 
-        // gathered input rows: lane (i16, g) reads x[row i16 of the sub-tile][8*g ...]
+        const uint16_t *Ag[NPROJ], *Aw[NPROJ];                // the group's A, this wave's A
+#pragma unroll
+        for (int pj = 0; pj < NPROJ; ++pj) {
+            Ag[pj] = units[(int64_t)key0 * p.n_proj + p.proj0 + pj].A;
+            Aw[pj] = units[(int64_t)t.key * p.n_proj + p.proj0 + pj].A;
+        }
+
+        // gathered input rows: lane (i16, g) reads x[row i16 of the sub-tile][8*g ...]; rows
+        // beyond the tile re-read its first row and are replaced by zeros
         const uint16_t *xp[SUB];
         bool rv[SUB];
 #pragma unroll
         for (int sub = 0; sub < SUB; ++sub) {
             const int r = sub * 16 + i16;
-            rv[sub] = r < t.n_rows;
-            xp[sub] = p.x;
-            if (rv[sub]) {
-                int s = p.perm[t.row0 + r];
-                if (p.src_row) s = p.src_row[s];
-                xp[sub] = p.x + (int64_t)s * p.ldx + g * 8;
-            }
+            rv[sub] = live && r < t.n_rows;
+            int s = p.perm[t.row0 + min(r, t.n_rows - 1)];
+            if (p.src_row) s = p.src_row[s];
+            xp[sub] = p.x + (int64_t)s * p.ldx + g * 8;
         }
 
-        const int part_end = min((part + 1) * p.kb_per_part, kblocks);
-        const int kb_begin = part * p.kb_per_part + wave * kb_per_wave;
-        const int kb_end = min(kb_begin + kb_per_wave, part_end);
+        const int kb_begin = part * p.kb_per_part;
+        const int kb_end = min(kb_begin + p.kb_per_part, kblocks);
+        const int n_stages = (kb_end - kb_begin + kStageKB - 1) / kStageKB;
 
         f32x4 acc[NPROJ][SUB][NB];
 #pragma unroll
@@ -74,74 +96,115 @@ __global__ __launch_bounds__(256, 2) void shrink_kernel(ShrinkParams p)
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb) acc[pj][sub][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-        for (int kb0 = kb_begin; kb0 < kb_end; kb0 += KB) {
-            u32x4 w[NPROJ][KB][NB];
-            u32x4 xv[SUB][KB];
+        // All loads are unconditional: a K block beyond the part re-reads the part's last
+        // block and is replaced by zeros (x as well: the padding may hold anything).
+        auto load_a = [&](int kb0, u32x4 (&a)[LOADS]) {
 #pragma unroll
-            for (int u = 0; u < KB; ++u) {
-                const int kb = kb0 + u;
-                const bool k_ok = kb < kb_end;
+            for (int i = 0; i < LOADS; ++i) {
+                const int b = 4 * i + wave;                   // operand block of the stage
+                const int kbi = b / BLK, rem = b - kbi * BLK;
+                const int pj = rem / NB, nb = rem - pj * NB;
+                const bool k_ok = kb0 + kbi < kb_end;
+                const int kb = k_ok ? kb0 + kbi : kb_end - 1;
+                const uint16_t *Ap = NPROJ == 2 && pj == 1 ? Ag[NPROJ - 1] : Ag[0];
+                const u32x4 v = ld16<false>(Ap + (((int64_t)kb * NB + nb) * 64 + lane) * 8);
+                a[i] = k_ok ? v : zero4;
+            }
+        };
+        auto store_a = [&](const u32x4 (&a)[LOADS], u32x4 *buf) {
+#pragma unroll
+            for (int i = 0; i < LOADS; ++i) buf[(4 * i + wave) * 64 + lane] = a[i];
+        };
+        auto load_x = [&](int kb0, u32x4 (&xv)[SUB][kStageKB]) {
+#pragma unroll
+            for (int kbi = 0; kbi < kStageKB; ++kbi) {
+                const bool k_ok = kb0 + kbi < kb_end;
+                const int kb = k_ok ? kb0 + kbi : kb_end - 1;
+                const bool c_ok = k_ok && kb * kKBlock + g * 8 < p.h_in;
+                const int c = c_ok ? kb * kKBlock : 0;
+#pragma unroll
+                for (int sub = 0; sub < SUB; ++sub) {
+                    const u32x4 v = ld16<false>(xp[sub] + c);
+                    xv[sub][kbi] = (c_ok && rv[sub]) ? v : zero4;
+                }
+            }
+        };
+        // one stage out of LDS: straight-line code, no global loads inside
+        auto compute = [&](const u32x4 *buf, const u32x4 (&xv)[SUB][kStageKB]) {
+#pragma unroll
+            for (int kbi = 0; kbi < kStageKB; ++kbi)
 #pragma unroll
                 for (int pj = 0; pj < NPROJ; ++pj)
 #pragma unroll
                     for (int nb = 0; nb < NB; ++nb) {
-                        w[pj][u][nb] = zero4;
-                        if (k_ok)
-                            w[pj][u][nb] = ld16<false>(
-                                Ap[pj] + (((int64_t)kb * NB + nb) * 64 + lane) * 8);
-                    }
-                const bool c_ok = k_ok && (kb * kKBlock + g * 8 < p.h_in);
+                        const u32x4 w = buf[((kbi * NPROJ + pj) * NB + nb) * 64 + lane];
 #pragma unroll
-                for (int sub = 0; sub < SUB; ++sub) {
-                    xv[sub][u] = zero4;
-                    if (c_ok && rv[sub])
-                        xv[sub][u] = ld16<false>(xp[sub] + kb * kKBlock);
+                        for (int sub = 0; sub < SUB; ++sub)
+                            acc[pj][sub][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                                as_bf16x8(w), as_bf16x8(xv[sub][kbi]), acc[pj][sub][nb], 0, 0, 0);
+                    }
+        };
+
+        u32x4 x0[SUB][kStageKB], x1[SUB][kStageKB];
+        if (same_key) {
+            u32x4 areg[LOADS];
+            load_a(kb_begin, areg);
+            load_x(kb_begin, x0);
+            store_a(areg, lds[0]);
+            __syncthreads();
+            for (int s = 0; s < n_stages; s += 2) {
+                const int kb0 = kb_begin + s * kStageKB;
+                load_a(kb0 + kStageKB, areg);
+                load_x(kb0 + kStageKB, x1);
+                __builtin_amdgcn_sched_barrier(0);            // all of the next stage's loads first
+                compute(lds[0], x0);
+                store_a(areg, lds[1]);
+                __syncthreads();
+                if (s + 1 < n_stages) {                       // uniform over the workgroup
+                    load_a(kb0 + 2 * kStageKB, areg);
+                    load_x(kb0 + 2 * kStageKB, x0);
+                    __builtin_amdgcn_sched_barrier(0);
+                    compute(lds[1], x1);
+                    store_a(areg, lds[0]);
+                    __syncthreads();
                 }
             }
-#pragma unroll
-            for (int u = 0; u < KB; ++u)
+        } else {
+            // a segment boundary inside the group: every wave reads the A of its own tile from
+            // global memory, one K block at a time (rare, so kept simple)
+            for (int kb = kb_begin; kb < kb_end; ++kb) {
+                const bool c_ok = kb * kKBlock + g * 8 < p.h_in;
+                u32x4 xv[SUB];
 #pragma unroll
                 for (int sub = 0; sub < SUB; ++sub) {
-                    if (sub < nsub) {
-#pragma unroll
-                        for (int pj = 0; pj < NPROJ; ++pj)
-#pragma unroll
-                            for (int nb = 0; nb < NB; ++nb)
-                                acc[pj][sub][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                                    as_bf16x8(w[pj][u][nb]), as_bf16x8(xv[sub][u]),
-                                    acc[pj][sub][nb], 0, 0, 0);
-                    }
+                    const u32x4 v = ld16<false>(xp[sub] + (c_ok ? kb * kKBlock : 0));
+                    xv[sub] = (c_ok && rv[sub]) ? v : zero4;
                 }
+#pragma unroll
+                for (int pj = 0; pj < NPROJ; ++pj)
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb) {
+                        const u32x4 w = ld16<false>(Aw[pj] + (((int64_t)kb * NB + nb) * 64 + lane) * 8);
+#pragma unroll
+                        for (int sub = 0; sub < SUB; ++sub)
+                            acc[pj][sub][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                                as_bf16x8(w), as_bf16x8(xv[sub]), acc[pj][sub][nb], 0, 0, 0);
+                    }
+            }
         }
 
-        // add the four waves' partial sums in a fixed order and store this part of v
+        // this wave's rows of this part of v: lane (row i16, group g) holds rank entries
+        // nb*16 + 4g .. +3 of its row
 #pragma unroll
         for (int pj = 0; pj < NPROJ; ++pj)
 #pragma unroll
             for (int sub = 0; sub < SUB; ++sub)
+                if (rv[sub]) {
 #pragma unroll
-                for (int nb = 0; nb < NB; ++nb) red[wave][pj][sub][nb][lane] = acc[pj][sub][nb];
-        __syncthreads();
-        constexpr int NOUT = NPROJ * SUB * NB * 64;
-        for (int o = tid; o < NOUT; o += 256) {
-            const int l = o & 63;
-            int rest = o >> 6;
-            const int nb = rest % NB;
-            rest /= NB;
-            const int sub = rest % SUB;
-            const int pj = rest / SUB;
-            const int row = sub * 16 + (l & 15);
-            const int j = nb * 16 + (l >> 4) * 4;
-            if (row < t.n_rows && j < R) {
-                f32x4 s = red[0][pj][sub][nb][l];
-                s += red[1][pj][sub][nb][l];
-                s += red[2][pj][sub][nb][l];
-                s += red[3][pj][sub][nb][l];
-                float *dst = p.v[pj] + ((int64_t)part * p.P + t.row0 + row) * R + j;
-                st16f(dst, s);
-            }
-        }
-        __syncthreads();
+                    for (int nb = 0; nb < NB; ++nb)
+                        st16f(p.v[pj] + ((int64_t)part * p.P + t.row0 + sub * 16 + i16) * R + nb * 16 + g * 4,
+                              acc[pj][sub][nb]);
+                }
     }
 }
 
@@ -149,19 +212,23 @@ template <int R>
 hipError_t launch_r(const ShrinkParams &p, hipStream_t s)
 {
     if (p.n_fused == 2)
-        hipLaunchKernelGGL((shrink_kernel<R, 2>), dim3(p.grid), dim3(256), 0, s, p);
+        hipLaunchKernelGGL((shrink_long_kernel<R, 2>), dim3(p.grid), dim3(256), 0, s, p, p.tiles, p.units,
+                           p.counts);
     else
-        hipLaunchKernelGGL((shrink_kernel<R, 1>), dim3(p.grid), dim3(256), 0, s, p);
+        hipLaunchKernelGGL((shrink_long_kernel<R, 1>), dim3(p.grid), dim3(256), 0, s, p, p.tiles, p.units,
+                           p.counts);
     return hipGetLastError();
 }
 
 }  // namespace
 
+int shrink_long_tiles() { return kLongTiles; }
+
 hipError_t launch_shrink(const ShrinkParams &p, hipStream_t s)
 {
     if (p.grid <= 0) return hipSuccess;
     switch (p.rank) {
-    case 16: return launch_r<16>(p, s);       // rank 8 always runs with 16-row tiles
+    case 16: return launch_r<16>(p, s);
     case 32: return launch_r<32>(p, s);
     case 64: return launch_r<64>(p, s);
     default: return hipErrorInvalidValue;
