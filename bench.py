@@ -149,6 +149,27 @@ def measure(name, args, steps, warmup, with_cpu_baseline):
         ms_per_step = (t1 - t0) * 1e3 / steps
         del graph
 
+    # ---- the same steps without the segment build (App. A.2.2 times shrink and expand only) --
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for it in range(steps):
+        for ph in phases[1:]:
+            ph.fn((warmup + it) % n_layers)
+    torch.cuda.synchronize()
+    nobuild_ms_per_step = (time.perf_counter() - t0) * 1e3 / steps
+
+    # ---- spread over the steps: an event between consecutive steps (stream launches; the
+    # event records add a little to every step, so the median sits above ms_per_step) -------
+    n_ev = min(steps, 200)
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(n_ev + 1)]
+    torch.cuda.synchronize()
+    evs[0].record()
+    for it in range(n_ev):
+        step(warmup + it)
+        evs[it + 1].record()
+    torch.cuda.synchronize()
+    per_step_us = np.array([evs[i].elapsed_time(evs[i + 1]) * 1e3 for i in range(n_ev)])
+
     # ---- per-launch durations with events on the launch stream ---------------------------
     # Each launch of the step is repeated back to back between two events (layers rotating,
     # so weights stay cold), which is how a kernel trace sees it; recording an event after
@@ -177,6 +198,9 @@ def measure(name, args, steps, warmup, with_cpu_baseline):
     total_bytes = acct["total"]
     res = dict(
         workload=name, ms_per_step=ms_per_step, stream_ms_per_step=stream_ms_per_step,
+        nobuild_ms_per_step=nobuild_ms_per_step,
+        step_us_p10=float(np.percentile(per_step_us, 10)), step_us_p50=float(np.percentile(per_step_us, 50)),
+        step_us_p90=float(np.percentile(per_step_us, 90)),
         tokens_per_s=w.tokens / (ms_per_step * 1e-3),
         pairs_per_s=w.pairs / (ms_per_step * 1e-3),
         step_gbs=total_bytes / (ms_per_step * 1e-3) / 1e9,
@@ -189,6 +213,27 @@ def measure(name, args, steps, warmup, with_cpu_baseline):
     del dp, db, run
     torch.cuda.empty_cache()
     return res
+
+
+def copy_ceiling_gbs():
+    """What a plain device-to-device copy of 1 GiB reaches on this machine (bytes read + written
+    per second): the practical ceiling for traffic that is part read, part write."""
+    import torch
+    src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        dst.copy_(src)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(10):
+        dst.copy_(src)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / 10
+    del src, dst
+    torch.cuda.empty_cache()
+    return 2 * (1 << 30) / (ms * 1e-3) / 1e9
 
 
 def read_traffic(workload, kernel):
@@ -262,6 +307,7 @@ def main():
         torch.cuda.synchronize()
         del src, dst
         torch.cuda.empty_cache()
+    ceiling = copy_ceiling_gbs()
     main_res = measure(args.workload, args, args.steps, args.warmup, not args.no_cpu_baseline)
     out = {
         "metric": "LoRA-delta tokens/s (MoE-LoRA decode layer call) on 1 MI355X",
@@ -277,8 +323,13 @@ def main():
                    else "stream launches",
                    "seed": args.seed, "segments": main_res["segments"], "rows": main_res["pairs"]},
         "stream_launch_ms_per_step": round(main_res["stream_ms_per_step"], 5),
+        "ms_per_step_without_segment_build": round(main_res["nobuild_ms_per_step"], 5),
+        "step_us_p10_p50_p90": [round(main_res["step_us_p10"], 2), round(main_res["step_us_p50"], 2),
+                                round(main_res["step_us_p90"], 2)],
         "hbm_gbs": round(main_res["step_gbs"], 1),
         "hbm_frac_of_peak": round(main_res["step_frac_of_peak"], 4),
+        "copy_ceiling_gbs": round(ceiling, 1),
+        "hbm_frac_of_copy_ceiling": round(main_res["step_gbs"] / ceiling, 4),
         "algorithmic_bytes_per_step": main_res["algorithmic_bytes"],
         "pairs_per_s": round(main_res["pairs_per_s"], 1),
         "phases": {k: {"us": round(v["us"], 2), "GB/s": round(v["gbs"], 1)}

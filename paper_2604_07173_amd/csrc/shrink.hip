@@ -117,17 +117,16 @@ __global__ __launch_bounds__(256, 2) void shrink_long_kernel(ShrinkParams p,
         };
         auto load_x = [&](int kb0, u32x4 (&xv)[SUB][kStageKB]) {
 #pragma unroll
-            for (int kbi = 0; kbi < kStageKB; ++kbi) {
-                const bool k_ok = kb0 + kbi < kb_end;
-                const int kb = k_ok ? kb0 + kbi : kb_end - 1;
-                const bool c_ok = k_ok && kb * kKBlock + g * 8 < p.h_in;
-                const int c = c_ok ? kb * kKBlock : 0;
+            for (int sub = 0; sub < SUB; ++sub)
 #pragma unroll
-                for (int sub = 0; sub < SUB; ++sub) {
-                    const u32x4 v = ld16<false>(xp[sub] + c);
+                for (int kbi = 0; kbi < kStageKB; ++kbi) {
+                    const bool k_ok = kb0 + kbi < kb_end;
+                    const int kb = k_ok ? kb0 + kbi : kb_end - 1;
+                    const bool c_ok = k_ok && kb * kKBlock + g * 8 < p.h_in;
+                    const int c = c_ok ? kb * kKBlock : 0;
+                    const u32x4 v = ld16<true>(xp[sub] + c);      // read once: nontemporal
                     xv[sub][kbi] = (c_ok && rv[sub]) ? v : zero4;
                 }
-            }
         };
         // one stage out of LDS: straight-line code, no global loads inside
         auto compute = [&](const u32x4 *buf, const u32x4 (&xv)[SUB][kStageKB]) {
