@@ -27,11 +27,9 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
-def _load():
-    global _lib
-    if _lib is None:
-        build()
-        lib = C.CDLL(_LIB)
+def _declare(lib):
+    """Argument and result types of the oracle's C functions on a loaded library."""
+    if True:
         lib.lora_oracle_delta.restype = C.c_int
         lib.lora_oracle_delta.argtypes = [
             C.c_int, C.c_int, C.c_int, C.c_int,
@@ -50,7 +48,14 @@ def _load():
         lib.lora_oracle_bf16_rne.argtypes = [C.c_double]
         lib.lora_oracle_bf16_to_f64.restype = C.c_double
         lib.lora_oracle_bf16_to_f64.argtypes = [C.c_uint16]
-        _lib = lib
+    return lib
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = _declare(C.CDLL(_LIB))
     return _lib
 
 

@@ -262,8 +262,6 @@ int do_shrink(const lora_pool *pool, int layer, const Group &g, const void *x, i
     sp.n_parts = ks.n_parts;
     sp.kb_per_part = ks.kb_per_part;
     sp.rank = pool->d.rank;
-    static const int nt = env_int("LORA_NONTEMPORAL", 1, 0, 1);
-    sp.nontemporal = nt;
     const int64_t items = tiles_upper_bound(pool, seg->P, seg->tile_rows) * ks.n_parts;
     if (seg->tile_rows == kDecodeTileRows) {
         static const int per_cu = env_int("LORA_DEC_SHRINK_WGS_PER_CU", 8, 1, 64);
@@ -306,8 +304,6 @@ int do_expand(const lora_pool *pool, int layer, const Group &g, const lora_segme
     ep.counts = seg->counts;
     ep.out_f32 = out_dtype == LORA_DTYPE_F32;
     ep.rank = pool->d.rank;
-    static const int nt = env_int("LORA_NONTEMPORAL", 1, 0, 1);
-    ep.nontemporal = nt;
     const int64_t tub = std::max<int64_t>(1, tiles_upper_bound(pool, seg->P, seg->tile_rows));
     if (seg->tile_rows == kDecodeTileRows) {
         // every wave works alone on wave items = (tile, projection, slice of 128-column chunks);

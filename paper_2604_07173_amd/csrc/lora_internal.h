@@ -83,7 +83,6 @@ struct ShrinkParams {
     int kb_per_part;
     int rank;
     int grid;
-    int nontemporal;         // stream the weights with nontemporal loads
     int wave_per_tile;       // decode kernel: every wave takes a whole tile (no K split across waves)
 };
 
@@ -111,7 +110,6 @@ struct ExpandParams {
     int out_f32;
     int rank;
     int grid;
-    int nontemporal;         // stream B and y with nontemporal accesses
 };
 
 hipError_t launch_pack_A(const PackParams &p, hipStream_t s);

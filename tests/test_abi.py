@@ -79,6 +79,10 @@ def test_calls_on_missing_pool_or_segments(lib):
     assert lib.lora_shrink(None, 0, 0, None, 0, None, C.byref(seg), None, None) == -5
     assert lib.lora_expand(None, 0, 0, None, C.byref(seg), None, 0, 0, None) == -5
     assert lib.lora_moe_apply(None, 0, 0, None, 0, None, C.byref(seg), None, None, 0, None, 0, None) == -5
+    assert lib.lora_apply(None, 0, 0, None, 0, None, C.byref(seg), None, 0, 0, None, None) == -5
+    assert lib.lora_apply_group(None, 0, 0, 2, None, 0, None, C.byref(seg), None, None, 0, None, 0,
+                                None) == -5
+    assert lib.lora_group_ws_bytes(None, 0, 2, 16) == 0
     assert lib.lora_pool_destroy(None) == -5
     assert lib.lora_v_bytes(None, 0, 16) == 0
     assert lib.lora_moe_ws_bytes(None, 16) == 0

@@ -311,3 +311,12 @@ def test_argument_errors_on_the_device_path():
     with pytest.raises(L.LoraError) as e:
         L.lora_moe_apply(dp.pool, 0, 0, x, 200, None, db.seg, db.y["p"], db.y["p"], 136, run.v)
     assert e.value.status == -2            # not a three-projection pool
+    y = db.y["p"]
+    small = torch.empty(16, dtype=torch.float32, device="cuda")
+    for n_proj, ws, status in [(2, run.v, -2), (4, run.v, -1), (0, run.v, -1), (1, small, -4)]:
+        with pytest.raises(L.LoraError) as e:      # group beyond the pool / too many / none / small ws
+            L.lora_apply_group(dp.pool, 0, 0, x, 200, None, db.seg, [y] * n_proj, [136] * n_proj, ws)
+        assert e.value.status == status, n_proj
+    with pytest.raises(L.LoraError) as e:
+        L.lora_apply(dp.pool, 0, 0, x, 200, None, db.seg, y, 128, run.v)
+    assert e.value.status == -2            # ldy smaller than the width
