@@ -16,13 +16,6 @@ namespace lora {
 
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 
-template <bool NT>
-__device__ inline u32x2 ld8(const void *p)
-{
-    const LORA_GLOBAL u32x2 *q = (const LORA_GLOBAL u32x2 *)p;
-    return NT ? __builtin_nontemporal_load(q) : *q;
-}
-
 template <int R>
 struct ExpandTile {
     static constexpr bool K16 = R <= 16;
@@ -49,21 +42,26 @@ struct ExpandTile {
     __device__ static inline void load_b(const uint16_t *Bp, int chunk, int lane, B &b)
     {
         const int g = lane >> 4, i16 = lane & 15;
+        if constexpr (R >= 32) {
 #pragma unroll
-        for (int blk = 0; blk < 8; ++blk)
+            for (int blk = 0; blk < 8; ++blk)
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                if constexpr (R >= 32) {
+                for (int ks = 0; ks < KS; ++ks) {
                     const int64_t off = (((((int64_t)chunk * 8 + blk) * KS + ks) * 4 + g) * 16 + i16) * 8;
                     b.r[blk][ks] = ld16<NT>(Bp + off);
-                } else if constexpr (R == 16) {
-                    const int64_t off = (((int64_t)chunk * 8 + blk) * 64 + lane) * 4;
-                    b.r[blk][ks] = ld8<NT>(Bp + off);
-                } else {
-                    const int64_t off = ((((int64_t)chunk * 8 + blk) * 2 + (g & 1)) * 16 + i16) * 4;
-                    b.r[blk][ks] = ld8<NT>(Bp + off);
                 }
+        } else {
+            // one 16-byte load per pair of sub-blocks; rank 8: lane groups 2,3 re-read the
+            // bytes of groups 0,1
+            constexpr int G = R / 4;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int64_t off = ((((int64_t)chunk * 4 + q) * G + (R == 16 ? g : (g & 1))) * 16 + i16) * 8;
+                const u32x4 v = ld16<NT>(Bp + off);
+                b.r[2 * q][0] = u32x2{v[0], v[1]};
+                b.r[2 * q + 1][0] = u32x2{v[2], v[3]};
             }
+        }
     }
 
     // KV fp32 values (already summed and scaled) -> this lane's part of the operand

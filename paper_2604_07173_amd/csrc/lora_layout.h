@@ -22,8 +22,9 @@
 //   rank >= 32 (v_mfma_f32_16x16x32_bf16): K steps of 32, ks = j/32; within a step lane
 //     group gl = (j%32)/8 holds t = j%8; a sub-block is 64 lanes x 16 bytes per K step.
 //   rank <= 16 (v_mfma_f32_16x16x16_bf16, four K values per lane): lane group gl = j/4
-//     holds t = j%4; a sub-block is rank/4 lane groups x 16 lanes x 8 bytes, so a wave reads
-//     it with one 8-byte load per lane and no two lanes of a rank-16 tile read the same bytes.
+//     holds t = j%4; the 8-byte operands of sub-blocks 2q and 2q+1 of a lane are adjacent, so
+//     a wave reads a pair of sub-blocks with one 16-byte load per lane (rank 16: 1 KiB
+//     contiguous, no two lanes read the same bytes).
 //   Columns are padded with zeros to a multiple of 128.
 #pragma once
 #include <stdint.h>
@@ -53,8 +54,9 @@ LORA_HD int64_t packB_index(int j, int d, int rank)
 {
     const int chunk = d >> 7, dd = d & 127, n = dd >> 3, blk = dd & 7;
     if (rank <= 16) {
+        // sub-blocks in pairs: a lane's operands of sub-blocks 2q and 2q+1 are adjacent
         const int G = rank >> 2, gl = j >> 2, t = j & 3;
-        return (((((int64_t)chunk * 8 + blk) * G + gl) * 16) + n) * 4 + t;
+        return ((((((int64_t)chunk * 4 + (blk >> 1)) * G + gl) * 16) + n) * 2 + (blk & 1)) * 4 + t;
     }
     const int KS = rank >> 5;
     const int ks = j >> 5, gl = (j & 31) >> 3, t = j & 7;

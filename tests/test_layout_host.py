@@ -71,6 +71,15 @@ def test_packB_is_a_bijection_and_groups_eight_columns_per_lane(exe, r):
     # a 128-column chunk occupies one contiguous span of 128*r values
     assert ix[:, :128].min() == 0 and ix[:, :128].max() == 128 * r - 1
     # columns 8n .. 8n+7 belong to MFMA column slot n of sub-blocks 0..7
-    per_blk = 128 * r // 8
-    for d in range(128):
-        assert ix[0, d] // per_blk == d % 8
+    if r >= 32:
+        per_blk = 128 * r // 8
+        for d in range(128):
+            assert ix[0, d] // per_blk == d % 8
+    else:
+        # rank <= 16: sub-blocks come in pairs; a lane's operands of sub-blocks 2q, 2q+1 are
+        # adjacent (one 16-byte load)
+        per_pair = 128 * r // 4
+        for d in range(128):
+            assert ix[0, d] // per_pair == (d % 8) // 2
+            assert (ix[0, d] // 4) % 2 == d % 2
+        assert ix[0, 1] == ix[0, 0] + 4
