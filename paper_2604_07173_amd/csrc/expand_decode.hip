@@ -5,7 +5,8 @@
 // wave adds the K parts of the tile's v in a fixed order, applies the adapter's scale and
 // splits the result into bf16 hi + lo planes held in MFMA operand registers (hi = v
 // truncated to bf16, lo = the rounded remainder, so the product sees about 16 mantissa bits
-// of v).  Main loop over the slice's chunks, software-pipelined two deep: while chunk c is
+// of v).  Main loop over the slice's chunks, software-pipelined two deep (the first two
+// chunks' loads are issued before v is fetched): while chunk c is
 // multiplied and written back, the packed B tile and the base-output rows of chunk c+1 are
 // already in flight (B with nontemporal loads: it is read once; y with ordinary accesses:
 // read-modify-write runs faster through the L2).  All loads in the loop are unconditional and the loop is specialised
@@ -91,26 +92,37 @@ struct ExpandWave {
         }
     }
 
-    // chunks [c0, c1), two in flight; every load in the loop body is unconditional
-    __device__ inline void run(int c0, int c1) const
+    // chunks in flight (three or four for the small rank-8 chunks measured no faster)
+    static constexpr int D = 2;
+
+    struct Stage {
+        typename Tile::B b;
+        YBuf y;
+    };
+
+    // issue the loads of the first D chunks of [c0, c1) (a slice shorter than D repeats its
+    // last chunk; the repeats are never used)
+    __device__ inline void prefetch(int c0, int c1, Stage (&st)[D]) const
     {
-        typename Tile::B b0, b1;
-        YBuf y0, y1;
-        load(c0, b0, y0);
+#pragma unroll
+        for (int k = 0; k < D; ++k) load(min(c0 + k, c1 - 1), st[k].b, st[k].y);
+    }
+
+    // chunks [c0, c1) after prefetch(): D in flight; every load in the loop body is
+    // unconditional
+    __device__ inline void run(int c0, int c1, Stage (&st)[D]) const
+    {
         int c = c0;
-        for (; c + 2 < c1; c += 2) {
-            load(c + 1, b1, y1);
-            compute_store(c, b0, y0);
-            load(c + 2, b0, y0);
-            compute_store(c + 1, b1, y1);
+        for (; c + D < c1; c += D) {
+#pragma unroll
+            for (int k = 0; k < D; ++k) {
+                compute_store(c + k, st[k].b, st[k].y);
+                load(min(c + k + D, c1 - 1), st[k].b, st[k].y);
+            }
         }
-        if (c + 1 < c1) {
-            load(c + 1, b1, y1);
-            compute_store(c, b0, y0);
-            compute_store(c + 1, b1, y1);
-        } else {
-            compute_store(c, b0, y0);
-        }
+#pragma unroll
+        for (int k = 0; k < D; ++k)
+            if (c + k < c1) compute_store(c + k, st[k].b, st[k].y);      // wave-uniform
     }
 };
 
@@ -134,6 +146,10 @@ __device__ inline void expand_item(const ExpandParams &p, const lora_tile &t, co
         const int dst = p.perm[t.row0 + min(r, t.n_rows - 1)];
         w.yrow[i] = static_cast<char *>(p.y[pj]) + (int64_t)dst * p.ldy[pj] * ESZ;
     }
+
+    // the first chunks' weights and base output: in flight while v is fetched
+    typename ExpandWave<R, F32, NI>::Stage st[ExpandWave<R, F32, NI>::D];
+    w.prefetch(c0, c1, st);
 
     // v operand: this lane's row slot i16 holds tile row (i16 % 4) * 4 + i16 / 4
     {
@@ -160,7 +176,7 @@ __device__ inline void expand_item(const ExpandParams &p, const lora_tile &t, co
             Tile::make_a(s, w.g, ks, w.a);
         }
     }
-    w.run(c0, c1);
+    w.run(c0, c1, st);
 }
 
 // tiles, units and counts are passed again as restrict-qualified kernel arguments: with a
