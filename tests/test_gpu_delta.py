@@ -163,6 +163,19 @@ def test_group_of_three_projections_matches_single_calls(rank, tokens, n):
         check_accumulate(bits_from_dev(db.y[p.name]), oracle_projection(b, ws, 0, j), p.name)
 
 
+@pytest.mark.parametrize("rank", [16, 64])
+def test_long_segment_kernels_with_many_short_segments(rank):
+    """P >= 64 * n_keys selects the 32-row-tile kernels; a Zipf draw over 24 adapters then
+    leaves many segments of a few rows next to long ones, so most four-tile groups of the
+    shrink straddle a segment boundary and the expand reloads B inside its tile groups."""
+    w = W.Workload("t", "dense", 24, 1, 1, rank, (W.Proj("p", 328, 264, "x"),), 2048, "zipf", 1.3)
+    b, ws, got, (dp, db, run) = run_dense(w, 51, "normal", drop=0.05)
+    assert db.seg.c.tile_rows == 32
+    lens = np.bincount(b.adapter_id[b.adapter_id >= 0], minlength=24)
+    assert lens.max() > 300 and (lens[lens > 0] < 32).sum() >= 4
+    check_accumulate(got, oracle_projection(b, ws, 0, 0), f"long kernels, short segments r{rank}")
+
+
 def test_shrink_output_matches_oracle_v_and_src_row():
     w = dense_workload(16, 2080, 136, n=4, tokens=72)
     b = W.make_batch(w, 16, hetero_scale=True)
