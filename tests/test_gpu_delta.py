@@ -176,6 +176,28 @@ def test_long_segment_kernels_with_many_short_segments(rank):
     check_accumulate(got, oracle_projection(b, ws, 0, 0), f"long kernels, short segments r{rank}")
 
 
+@pytest.mark.parametrize("tokens", [1, 40, 5000])
+def test_batch_without_any_adapter_leaves_everything_untouched(tokens):
+    """Every row has id -1: no segment, no tile; y keeps its bits (both kernel families)."""
+    w = dense_workload(16, 200, 136, n=3, tokens=tokens)
+    b = W.make_batch(w, 61, y_mode="normal")
+    b.adapter_id[:] = -1
+    ws = W.make_weights(w, 61, bank_elems=1 << 20)
+    dp, db = DevicePool(ws, b.scale), DeviceBatch(b)
+    run = LayerRunner(dp, db)
+    run.build_segments()
+    assert db.seg.counts.cpu().tolist()[:3] == [0, 0, 0]
+    run.apply(0)
+    torch.cuda.synchronize()
+    assert np.array_equal(bits_from_dev(db.y["p"]), b.y_in["p"])
+
+
+def test_single_row_batch():
+    w = dense_workload(64, 264, 392, n=2, tokens=1)
+    b, ws, got, _ = run_dense(w, 62, "normal")
+    check_accumulate(got, oracle_projection(b, ws, 0, 0), "one row")
+
+
 def test_shrink_output_matches_oracle_v_and_src_row():
     w = dense_workload(16, 2080, 136, n=4, tokens=72)
     b = W.make_batch(w, 16, hetero_scale=True)
