@@ -106,3 +106,53 @@ def test_lower_adapter_rank_is_zero_padded():
     assert np.array_equal(bits_from_dev(A_out)[:, :8], A) and not bits_from_dev(A_out)[:, 8:].any()
     assert np.array_equal(bits_from_dev(B_out)[:8], B) and not bits_from_dev(B_out)[8:].any()
     assert L.lora_pool_unit_layout(pool, 1, 0, 0, 0)["rank"] == 8
+
+
+def test_layerwise_loading_on_a_second_stream_overlaps_with_compute():
+    """Sec. 5.3: an adapter is loaded layer by layer while earlier layers already compute.
+    Host-pinned windows are copied and repacked on a loading stream, one event per layer; the
+    compute stream waits for a layer's event, then runs that layer.  Every layer's output
+    must match the oracle."""
+    from gpu_common import check_accumulate, oracle_projection
+    from paper_2604_07173_amd.harness import DeviceBatch, LayerRunner
+
+    n_layers = 4
+    w = W.Workload("t", "dense", 6, 1, 1, 16, (W.Proj("p", 264, 392, "x"),), 80, "uniform", 0.0)
+    b = W.make_batch(w, 71, y_mode="normal", hetero_scale=True)
+    ws = W.make_weights(w, 71, n_layers=n_layers, bank_elems=1 << 20)
+    desc = L.PoolDesc(w.n_adapters, n_layers, 1, [(264, 392)], 16, scale=[float(s) for s in b.scale])
+    slab = torch.zeros(L.lora_pool_bytes(desc), dtype=torch.uint8, device="cuda")
+    pool = L.lora_register_pool(desc, slab)
+    torch.cuda.synchronize()
+
+    win = (264 + 392) * 16                                  # elements of one (adapter, layer) window
+    host = [[torch.from_numpy(ws.bank[int(ws.window[a, l]):int(ws.window[a, l]) + win].view(np.int16).copy())
+             .pin_memory() for a in range(w.n_adapters)] for l in range(n_layers)]
+    staging = [[torch.empty(win, dtype=torch.int16, device="cuda") for _ in range(w.n_adapters)]
+               for _ in range(n_layers)]
+    load_stream, compute_stream = torch.cuda.Stream(), torch.cuda.Stream()
+    ready = [torch.cuda.Event() for _ in range(n_layers)]
+
+    db = DeviceBatch(b)
+    holder = type("P", (), {})()                            # what LayerRunner needs of a DevicePool
+    holder.workload, holder.pool, holder.device = w, pool, "cuda"
+    run = LayerRunner(holder, db)
+    ys = []
+    with torch.cuda.stream(load_stream):
+        for l in range(n_layers):
+            for a in range(w.n_adapters):
+                staging[l][a].copy_(host[l][a], non_blocking=True)
+                L.lora_pool_load_adapter_layer(pool, a, l, staging[l][a], stream=load_stream)
+            ready[l].record(load_stream)
+    with torch.cuda.stream(compute_stream):
+        run.build_segments(stream=compute_stream)
+        for l in range(n_layers):
+            compute_stream.wait_event(ready[l])
+            y = to_dev(b.y_in["p"])
+            x = db.inputs["x"]
+            L.lora_apply(pool, l, 0, x, x.shape[1], None, db.seg, y, y.shape[1], run.v,
+                         stream=compute_stream)
+            ys.append(y)
+    torch.cuda.synchronize()
+    for l in range(n_layers):
+        check_accumulate(bits_from_dev(ys[l]), oracle_projection(b, ws, l, 0), f"layer {l}")
