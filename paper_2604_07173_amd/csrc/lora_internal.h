@@ -20,7 +20,7 @@ struct Unit {
 };
 static_assert(sizeof(Unit) == 32, "table entry is 32 bytes");
 
-constexpr int kTileRows = 32;        // rows per tile of the general kernels
+constexpr int kTileRows = 32;        // rows per tile of the long-segment kernels
 constexpr int kDecodeTileRows = 16;  // rows per tile of the decode kernels
 constexpr int kKBlock = 32;          // K elements per MFMA step (v_mfma_f32_16x16x32_bf16)
 constexpr int kColChunk = 128;       // output columns one wave owns in expand
@@ -90,8 +90,7 @@ struct ExpandParams {
     const Unit *units;
     int n_proj;
     int proj0;
-    int n_fused;             // 1 .. kMaxFused consecutive projections (their h_out may differ in
-                             // the decode kernel; the general kernel wants them equal)
+    int n_fused;             // 1 .. kMaxFused consecutive projections; their widths may differ
     const float *v[kMaxFused];
     int n_parts;
     int P;
