@@ -5,6 +5,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <cmath>
 #include <new>
 #include <string>
 #include <vector>
@@ -306,18 +307,26 @@ int do_expand(const lora_pool *pool, int layer, const Group &g, const lora_segme
     ep.rank = pool->d.rank;
     const int64_t tub = std::max<int64_t>(1, tiles_upper_bound(pool, seg->P, seg->tile_rows));
     if (seg->tile_rows == kDecodeTileRows) {
-        // every wave works alone on wave items = (tile, projection, slice of 128-column chunks);
-        // chunks per wave item: long enough to amortise the per-item prologue, short enough
-        // that a small batch still yields a few thousand wave items
+        // every wave works alone on wave items = (tile, projection, slice of 128-column chunks).
+        // Chunks per item: an item should move about item_bytes (its prologue - row indices, v -
+        // costs a few load latencies), but a small batch must still yield a few thousand items;
+        // the grid holds several times more workgroups than are resident, so that the hardware
+        // hands out items as waves finish and tiles of different heights balance out.
         static const int cpi_max = env_int("LORA_DEC_CHUNKS_PER_ITEM", 8, 1, 4096);
+        static const int item_bytes = env_int("LORA_DEC_ITEM_BYTES", 12288, 1024, 1 << 24);
         static const int want_items = env_int("LORA_DEC_EXPAND_ITEMS", 4096, 1, 1 << 22);
-        static const int per_cu = env_int("LORA_DEC_EXPAND_WGS_PER_CU", 4, 1, 64);
+        static const int per_cu = env_int("LORA_DEC_EXPAND_WGS_PER_CU", 16, 1, 64);
         ep.proj0 = g.proj0;
         ep.n_fused = g.n;
         int64_t chunks_per_tile = 0;
         for (int j = 0; j < g.n; ++j) chunks_per_tile += chunks_of(pool->d.proj[g.proj0 + j].h_out);
         const int64_t units = tub * chunks_per_tile;
-        const int cpi = (int)std::max<int64_t>(1, std::min<int64_t>(cpi_max, units / want_items));
+        // bytes of one chunk of an average tile: its B plus the read-modify-write of its rows
+        const double rows_per_tile = (double)seg->P / (double)tub;
+        const double chunk_bytes = kColChunk * pool->d.rank * 2.0 +
+                                   rows_per_tile * kColChunk * (out_dtype == LORA_DTYPE_F32 ? 8.0 : 4.0);
+        int cpi = (int)std::lround(item_bytes / chunk_bytes);
+        cpi = (int)std::max<int64_t>(1, std::min<int64_t>(std::min(cpi, cpi_max), units / want_items));
         ep.slice0[0] = 0;
         for (int j = 0; j < g.n; ++j) {
             ep.v[j] = g.v[j];
@@ -325,9 +334,13 @@ int do_expand(const lora_pool *pool, int layer, const Group &g, const lora_segme
             ep.ldy[j] = g.ldy[j];
             ep.h_out[j] = pool->d.proj[g.proj0 + j].h_out;
             ep.n_chunks[j] = chunks_of(ep.h_out[j]);
-            // no empty slice: a row is cut into n_slices pieces of ceil(n_chunks / n_slices) chunks
+            // no empty slice: a row is cut into n_slices pieces of cps = ceil(n_chunks / n_slices)
+            // chunks; cps even, because the kernel keeps two chunks in flight with unconditional
+            // loads and a piece of odd length costs it one chunk loaded twice
             const int want = std::max(1, (ep.n_chunks[j] + cpi - 1) / cpi);
-            const int cps = (ep.n_chunks[j] + want - 1) / want;
+            int cps = (ep.n_chunks[j] + want - 1) / want;
+            if (cpi > 1) cps = std::min(ep.n_chunks[j], (cps + 1) & ~1);     // cpi 1: a small batch, items first
+            ep.cps[j] = cps;
             ep.n_slices[j] = (ep.n_chunks[j] + cps - 1) / cps;
             ep.slice0[j + 1] = ep.slice0[j] + ep.n_slices[j];
         }

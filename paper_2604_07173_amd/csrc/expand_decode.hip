@@ -200,7 +200,7 @@ __global__ __launch_bounds__(256, 2) void expand16_kernel(ExpandParams p,
         const int rem = item - tile_ix * per_tile;
         const int pj = (rem >= p.slice0[1] ? 1 : 0) + (p.n_fused > 2 && rem >= p.slice0[2] ? 1 : 0);
         const int slice = rem - p.slice0[pj];
-        const int cps = (p.n_chunks[pj] + p.n_slices[pj] - 1) / p.n_slices[pj];   // chunks per slice
+        const int cps = p.cps[pj];                                // chunks per slice
         const int c0 = slice * cps, c1 = min(c0 + cps, p.n_chunks[pj]);
         if (c0 >= c1) continue;
         const lora_tile t = tiles[tile_ix];

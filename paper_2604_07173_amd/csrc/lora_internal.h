@@ -102,6 +102,7 @@ struct ExpandParams {
     int h_out[kMaxFused];
     int n_chunks[kMaxFused]; // 128-column chunks
     int n_slices[kMaxFused]; // decode kernel: wave items per (tile, projection)
+    int cps[kMaxFused];      // decode kernel: chunks per wave item (the last of a row may have fewer)
     int slice0[kMaxFused + 1];   // decode kernel: first wave item of a projection within a tile
     void *img[kMaxFused];    // long-segment kernel: operand images of the 16-row sub-tiles
     int image_grid;          // long-segment kernel: workgroups of the image launch
