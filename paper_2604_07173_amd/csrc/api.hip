@@ -354,7 +354,7 @@ int do_expand(const lora_pool *pool, int layer, const Group &g, const lora_segme
     }
     // long segments: operand images of the sub-tiles behind the K parts in each projection's
     // slice of the workspace, then wave items = (group of tiles, projection, 128-column chunk)
-    static const int per_cu = env_int("LORA_EXPAND_WGS_PER_CU", 8, 1, 64);
+    static const int per_cu = env_int("LORA_EXPAND_WGS_PER_CU", 32, 1, 64);
     ep.proj0 = g.proj0;
     ep.n_fused = g.n;
     ep.slice0[0] = 0;
