@@ -325,7 +325,9 @@ int do_expand(const lora_pool *pool, int layer, const Group &g, const lora_segme
         const double rows_per_tile = (double)seg->P / (double)tub;
         const double chunk_bytes = kColChunk * pool->d.rank * 2.0 +
                                    rows_per_tile * kColChunk * (out_dtype == LORA_DTYPE_F32 ? 8.0 : 4.0);
-        int cpi = (int)std::lround(item_bytes / chunk_bytes);
+        // at least two chunks (the kernel keeps two in flight) unless the batch is so small
+        // that single-chunk items are needed to occupy the chip
+        int cpi = std::max(2, (int)std::lround(item_bytes / chunk_bytes));
         cpi = (int)std::max<int64_t>(1, std::min<int64_t>(std::min(cpi, cpi_max), units / want_items));
         ep.slice0[0] = 0;
         for (int j = 0; j < g.n; ++j) {
