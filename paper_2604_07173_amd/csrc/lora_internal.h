@@ -57,6 +57,7 @@ struct SegParams {
     int tile_rows;
     int passes;              // radix passes of 8 bits over the key
     int key_bits;            // bits of the largest key
+    int bucket_shift;        // set by launch_segments: log2 of counter words per thread
     int32_t *perm;
     int32_t *seg_start;
     int32_t *seg_key;

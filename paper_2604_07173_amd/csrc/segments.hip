@@ -37,29 +37,37 @@ struct ScanLds {
     int mn[kWaves];
 };
 
+// inclusive prefix sum over the 64 lanes on the cross-lane data path (no LDS round trips):
+// shifts inside the rows of 16 lanes, then lane 15 of a row added to the next row (rows 1
+// and 3), then lane 31 added to rows 2 and 3.  A lane without a source adds 0.
+__device__ inline unsigned wave_incl_sum(unsigned x)
+{
+    x += (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x111, 0xf, 0xf, false);   // row_shr:1
+    x += (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x112, 0xf, 0xf, false);   // row_shr:2
+    x += (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x114, 0xf, 0xf, false);   // row_shr:4
+    x += (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x118, 0xf, 0xf, false);   // row_shr:8
+    x += (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x142, 0xa, 0xf, false);   // row_bcast:15
+    x += (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x143, 0xc, 0xf, false);   // row_bcast:31
+    return x;
+}
+
 // exclusive prefix sum over the workgroup, plus the total
 __device__ __noinline__ int block_excl_sum(int v, int *total, volatile int *wave_sums)
 {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    int inc = v;
-#pragma unroll 1
-    for (int o = 1; o < 64; o <<= 1) {
-        int t = __shfl_up(inc, o, 64);
-        if (lane >= o) inc += t;
-    }
+    const int inc = (int)wave_incl_sum((unsigned)v);
     __syncthreads();
     if (lane == 63) wave_sums[w] = inc;
     __syncthreads();
-    // wave totals: lane k < 16 fetches total k, a wave reduction does the rest
-    const int mine = lane < kWaves ? wave_sums[lane] : 0;
-    int tot = mine, base = lane < w ? mine : 0;
-#pragma unroll 1
-    for (int o = 8; o > 0; o >>= 1) {
-        tot += __shfl_xor(tot, o, 64);
-        base += __shfl_xor(base, o, 64);
+    // wave totals: lane k of the first 16 fetches total k, scalar reads of the lanes add them
+    const int mine = wave_sums[lane & (kWaves - 1)];
+    int tot = 0, base = 0;
+#pragma unroll
+    for (int k = 0; k < kWaves; ++k) {
+        const int t = __builtin_amdgcn_readlane(mine, k);
+        tot += t;
+        base += k < w ? t : 0;
     }
-    tot = __shfl(tot, 0, 64);
-    base = __shfl(base, 0, 64);
     *total = tot;
     return base + inc - v;
 }
@@ -140,7 +148,51 @@ __device__ inline unsigned lanes_below(Match m)
     return __builtin_amdgcn_mbcnt_hi(m.hi, __builtin_amdgcn_mbcnt_lo(m.lo, 0u));
 }
 
-__global__ __launch_bounds__(kThreads) void segments_kernel(SegParams p)
+constexpr unsigned kNoKey = 0xFFFFFFFFu;               // row without adapter: left out of the order
+
+// key of a row from its ids, or kNoKey; ids that are neither valid nor -1 are reported in `bad`
+__device__ inline unsigned row_key(const SegParams &p, int a, int e, unsigned &bad)
+{
+    const bool a_ok = a >= 0 && a < p.n_adapters;
+    const bool e_ok = e >= 0 && e < p.n_experts;
+    const bool ok = a_ok && e_ok;
+    if (a != -1 && !ok)
+        bad |= (a_ok ? 0u : (unsigned)LORA_STATUS_BAD_ADAPTER) |
+               (e_ok ? 0u : (unsigned)LORA_STATUS_BAD_EXPERT);
+    return ok ? (unsigned)a * (unsigned)p.n_experts + (unsigned)e : kNoKey;
+}
+
+// key_of[i] for all rows; `each(i, key)` is called once per row.  The id loads of four rows
+// are issued before the first is used (the ids come from HBM; one round trip per row would
+// otherwise dominate large batches).
+template <class F>
+__device__ inline void all_row_keys(const SegParams &p, unsigned *key_of, unsigned &bad, F each)
+{
+    constexpr int U = 4;
+    const int tid = threadIdx.x;
+#pragma unroll 1
+    for (int i0 = tid; i0 < p.P; i0 += U * kThreads) {
+        int a[U], e[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int i = min(i0 + u * kThreads, p.P - 1);     // a valid row: the load is unconditional
+            a[u] = p.adapter_id[i];
+            e[u] = p.expert_id ? p.expert_id[i] : 0;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int i = i0 + u * kThreads;
+            if (i < p.P) {
+                const unsigned k = row_key(p, a[u], e[u], bad);
+                key_of[i] = k;
+                each(i, k);
+            }
+        }
+    }
+}
+
+// The radix path, whole: keys, passes, boundaries, tiles, counts.
+__device__ __forceinline__ void radix_body(const SegParams &p)
 {
     __shared__ unsigned hist[kWaves][kBins];
     __shared__ ScanLds scan;
@@ -155,7 +207,6 @@ __global__ __launch_bounds__(kThreads) void segments_kernel(SegParams p)
     uint16_t *order[2] = {reinterpret_cast<uint16_t *>(key_of + P_pad),          // [P_pad] each
                           reinterpret_cast<uint16_t *>(key_of + P_pad) + P_pad};
     const unsigned n_keys = (unsigned)p.n_adapters * (unsigned)p.n_experts;
-    constexpr unsigned kNoKey = 0xFFFFFFFFu;               // row without adapter: dropped by pass 0
     const int items = (P + kThreads - 1) / kThreads;       // 64-row groups per wave
     const int wave_base = w * items * 64;
     const bool park = n_keys <= 0x10000u;                  // room for a 16-bit rank above the key
@@ -172,20 +223,7 @@ __global__ __launch_bounds__(kThreads) void segments_kernel(SegParams p)
     {
         int n_active = 0;
         unsigned bad = 0;
-#pragma unroll 1
-        for (int i = tid; i < P; i += kThreads) {
-            const int a = p.adapter_id[i];
-            const int e = p.expert_id ? p.expert_id[i] : 0;
-            const bool a_ok = a >= 0 && a < p.n_adapters;
-            const bool e_ok = e >= 0 && e < p.n_experts;
-            const bool none = a == -1;
-            const bool ok = a_ok && e_ok;
-            key_of[i] = ok ? (unsigned)a * (unsigned)p.n_experts + (unsigned)e : kNoKey;
-            n_active += ok ? 1 : 0;
-            if (!none && !ok)
-                bad |= (a_ok ? 0u : (unsigned)LORA_STATUS_BAD_ADAPTER) |
-                       (e_ok ? 0u : (unsigned)LORA_STATUS_BAD_EXPERT);
-        }
+        all_row_keys(p, key_of, bad, [&](int, unsigned k) { n_active += k != kNoKey ? 1 : 0; });
         if (bad) atomicOr(&status_bits, bad);          // OR and + are order-independent
 #pragma unroll 1
         for (int o = 32; o > 0; o >>= 1) n_active += __shfl_xor(n_active, o, 64);
@@ -336,6 +374,224 @@ __global__ __launch_bounds__(kThreads) void segments_kernel(SegParams p)
     }
 }
 
+__global__ __launch_bounds__(kThreads) void segments_kernel(SegParams p)
+{
+    radix_body(p);
+}
+
+// ---- bucket path ---------------------------------------------------------------------------
+// For batches of many short segments (decode): one LDS counter per key instead of radix
+// passes over the key bits.
+//   1. count the rows of every key with LDS adds (a sum: the order of the adds is immaterial);
+//   2. thread t owns a contiguous range of keys: an exclusive scan over the counts gives
+//      every key its start; the keys that occur are the segments, so they are listed in LDS
+//      and the segment records and tiles are then written one segment per thread;
+//   3. every row takes a place inside its key's range with a fetching LDS add; which place
+//      depends on the order the adds execute in, so
+//   4. every row is re-ranked inside its bucket by the number of rows of the bucket with a
+//      smaller row index: the final order is by (key, row index), unique, hence bit-identical
+//      run to run and identical to the stable sort of the radix path.
+// Step 4 costs bucket length per row; if one key holds more than kMaxBucket rows the
+// workgroup drops this attempt and runs the radix path (a workgroup-uniform decision).
+//
+// Two 16-bit counters share a 32-bit LDS word (a batch has at most 16384 rows, so neither
+// half overflows and positions fit 16 bits).  The words are skewed by one word per
+// thread-owned range so that the threads' range walks hit different banks.
+constexpr int kMaxBucket = 256;
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+
+// exclusive prefix sums of two values over the workgroup, plus their totals; one barrier
+__device__ inline void block_excl_sum2(unsigned a, unsigned b, volatile unsigned (*wave_sums)[2],
+                                       unsigned *a_before, unsigned *b_before, unsigned *a_total,
+                                       unsigned *b_total)
+{
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const unsigned ia = wave_incl_sum(a), ib = wave_incl_sum(b);
+    if (lane == 63) {
+        wave_sums[w][0] = ia;
+        wave_sums[w][1] = ib;
+    }
+    __syncthreads();
+    const unsigned ma = wave_sums[lane & (kWaves - 1)][0], mb = wave_sums[lane & (kWaves - 1)][1];
+    unsigned ta = 0, tb = 0, ba = 0, bb = 0;
+#pragma unroll
+    for (int k = 0; k < kWaves; ++k) {
+        const unsigned xa = (unsigned)__builtin_amdgcn_readlane((int)ma, k);
+        const unsigned xb = (unsigned)__builtin_amdgcn_readlane((int)mb, k);
+        ta += xa;
+        tb += xb;
+        ba += k < w ? xa : 0u;
+        bb += k < w ? xb : 0u;
+    }
+    *a_before = ba + ia - a;
+    *b_before = bb + ib - b;
+    *a_total = ta;
+    *b_total = tb;
+}
+
+__global__ __launch_bounds__(kThreads) void segments_bucket_kernel(SegParams p)
+{
+    __shared__ unsigned wave_sums[kWaves][2];
+    __shared__ unsigned status_bits;
+    __shared__ int n_active_total;
+    __shared__ unsigned longest;
+    extern __shared__ __attribute__((aligned(16))) unsigned char dyn_lds[];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int P = p.P;
+    const int P_pad = (P + 63) & ~63;
+    const int shift = p.bucket_shift;                 // log2 of the counter words per thread
+    const int wpt = 1 << shift;
+    const int n_cnt = (kThreads << shift) + kThreads; // counter words incl. the skew
+    unsigned *key_of = reinterpret_cast<unsigned *>(dyn_lds);           // [P_pad]
+    unsigned *cnt = key_of + P_pad;                                     // [n_cnt]
+    unsigned *tmp = cnt + n_cnt;                                        // [P_pad] row | key << 16
+    unsigned *seglist = tmp;               // key | first tile << 16 per segment, before tmp is used
+    auto slot = [&](unsigned word) { return word + (shift ? word >> shift : 0u); };
+    auto half_of = [&](unsigned key) { return (cnt[slot(key >> 1)] >> ((key & 1u) * 16u)) & 0xFFFFu; };
+
+    if (tid == 0) {
+        status_bits = 0;
+        n_active_total = 0;
+        longest = 0;
+    }
+    for (int b = tid; b < n_cnt; b += kThreads) cnt[b] = 0;
+    __syncthreads();
+
+    // ---- 1. keys and counts --------------------------------------------------------------
+    {
+        int n_active = 0;
+        unsigned bad = 0;
+        all_row_keys(p, key_of, bad, [&](int, unsigned k) {
+            if (k != kNoKey) {
+                ++n_active;
+                atomicAdd(&cnt[slot(k >> 1)], 1u << ((k & 1u) * 16u));
+            }
+        });
+        if (bad) atomicOr(&status_bits, bad);
+#pragma unroll 1
+        for (int o = 32; o > 0; o >>= 1) n_active += __shfl_xor(n_active, o, 64);
+        if (lane == 0 && n_active) atomicAdd(&n_active_total, n_active);
+    }
+    __syncthreads();
+
+    // ---- 2. scan over the keys; segments and tiles ----------------------------------------
+    const int TR = p.tile_rows;                       // a power of two
+    const int tr_shift = 31 - __clz(TR);
+    const unsigned w0 = (unsigned)tid << shift;       // my counter words: w0 .. w0 + wpt - 1
+    unsigned rs_before, rs_total, t_before, t_total;  // rows | segments << 16, and tiles
+    unsigned long long occupied = 0;                  // my keys that have rows (wpt <= 32 words)
+    {
+        unsigned rows = 0, tiles = 0, mx = 0;
+#pragma unroll 1
+        for (int j = 0; j < wpt; ++j) {
+            const unsigned c = cnt[slot(w0 + j)];
+            const unsigned lo = c & 0xFFFFu, hi = c >> 16;
+            rows += lo + hi;
+            tiles += ((lo + TR - 1) >> tr_shift) + ((hi + TR - 1) >> tr_shift);
+            mx = max(mx, max(lo, hi));
+            occupied |= (unsigned long long)((lo ? 1u : 0u) | (hi ? 2u : 0u)) << (2 * j);
+        }
+        if (mx > kMaxBucket) atomicMax(&longest, mx);
+        // a batch has at most 16384 rows, so rows and segments share a word
+        block_excl_sum2(rows | ((unsigned)__popcll(occupied) << 16), tiles, wave_sums, &rs_before,
+                        &t_before, &rs_total, &t_total);
+    }
+    if (longest > kMaxBucket) {        // same value in every thread: read after the scan's barrier
+        __syncthreads();
+        radix_body(p);
+        return;
+    }
+    const int P_act = (int)(rs_total & 0xFFFFu);
+    const int S = (int)(rs_total >> 16);
+    const int n_tiles = (int)t_total;
+    {
+        // list of the occupied keys with the first tile of each (a loop over my set bits
+        // only: most keys of a large key space are empty), then the start of every key in
+        // place of its count
+        int sidx = (int)(rs_before >> 16);
+        unsigned tix = t_before;
+#pragma unroll 1
+        for (unsigned long long rest = occupied; rest; rest &= rest - 1) {
+            const int b = __ffsll((long long)rest) - 1;
+            const unsigned n = (cnt[slot(w0 + (b >> 1))] >> (16 * (b & 1))) & 0xFFFFu;
+            seglist[sidx++] = (w0 * 2 + b) | (tix << 16);
+            tix += (n + TR - 1) >> tr_shift;
+        }
+        unsigned at = rs_before & 0xFFFFu;
+#pragma unroll 1
+        for (int j = 0; j < wpt; ++j) {
+            const unsigned c = cnt[slot(w0 + j)];
+            const unsigned lo = c & 0xFFFFu, hi = c >> 16;
+            cnt[slot(w0 + j)] = at | ((at + lo) << 16);
+            at += lo + hi;
+        }
+    }
+    __syncthreads();
+    // segment records and tiles, one segment per thread and turn
+#pragma unroll 1
+    for (int sidx = tid; sidx < S; sidx += kThreads) {
+        const unsigned me = seglist[sidx];
+        const unsigned next = seglist[min(sidx + 1, S - 1)];
+        const int key = (int)(me & 0xFFFFu);
+        const int pos = (int)half_of(me & 0xFFFFu);
+        const int n = (sidx + 1 < S ? (int)half_of(next & 0xFFFFu) : P_act) - pos;
+        int tix = (int)(me >> 16);
+        p.seg_start[sidx] = pos;
+        p.seg_key[sidx] = key;
+#pragma unroll 1
+        for (int r = 0; r < n; r += TR) {
+            lora_tile t;
+            t.key = key;
+            t.row0 = pos + r;
+            t.n_rows = min(TR, n - r);
+            t.seg = sidx;
+            p.tiles[tix++] = t;
+        }
+    }
+    __syncthreads();
+
+    // ---- 3. a place in the key's range for every row --------------------------------------
+#pragma unroll 1
+    for (int i = tid; i < P; i += kThreads) {
+        const unsigned k = key_of[i];
+        if (k != kNoKey) {
+            const unsigned sh = (k & 1u) * 16u;
+            const unsigned old = atomicAdd(&cnt[slot(k >> 1)], 1u << sh);
+            tmp[(old >> sh) & 0xFFFFu] = (unsigned)i | (k << 16);
+        }
+    }
+    if (tid < 4 && P_act + tid < ((P_act + 3) & ~3)) tmp[P_act + tid] = 0xFFFFFFFFu;   // filler
+    __syncthreads();
+
+    // ---- 4. order inside the bucket by row index -------------------------------------------
+    // after step 3 a key's counter holds the end of its range = the start of the next key's
+    // The bucket is read in aligned groups of four words; words of other keys (and the
+    // filler behind the last row) fall outside [key << 16, mine) and count as not smaller.
+#pragma unroll 1
+    for (int pos = tid; pos < P_act; pos += kThreads) {
+        const unsigned mine = tmp[pos];
+        const unsigned k = mine >> 16, row = mine & 0xFFFFu, base = mine & 0xFFFF0000u;
+        const int e = (int)half_of(k);
+        const int b = k ? (int)half_of(k - 1) : 0;
+        int rank = 0;
+#pragma unroll 1
+        for (int j = b & ~3; j < e; j += 4) {
+            const u32x4 t = *reinterpret_cast<const u32x4 *>(tmp + j);
+            rank += (t[0] - base < row ? 1 : 0) + (t[1] - base < row ? 1 : 0) +
+                    (t[2] - base < row ? 1 : 0) + (t[3] - base < row ? 1 : 0);
+        }
+        p.perm[b + rank] = (int32_t)row;
+    }
+    if (tid == 0) {
+        p.seg_start[S] = P_act;
+        p.counts[0] = S;
+        p.counts[1] = P_act;
+        p.counts[2] = n_tiles;
+        p.counts[3] = 0;
+        p.status[0] = status_bits;
+    }
+}
 }  // namespace
 
 size_t segments_lds_bytes(int P)
@@ -344,8 +600,42 @@ size_t segments_lds_bytes(int P)
     return P_pad * 4 + 2 * P_pad * 2;
 }
 
-hipError_t launch_segments(const SegParams &p, hipStream_t s)
+// log2 of the counter words a thread of the bucket path owns
+static int bucket_shift_of(unsigned n_keys)
 {
+    const unsigned n_words = (n_keys + 1) / 2;
+    int shift = 0;
+    while (((unsigned)kThreads << shift) < n_words) ++shift;
+    return shift;
+}
+
+// dynamic LDS of the bucket path (it may fall back to the radix path inside the kernel)
+static size_t bucket_lds_bytes(int P, unsigned n_keys)
+{
+    const size_t P_pad = ((size_t)P + 63) & ~(size_t)63;
+    const size_t n_cnt = ((size_t)kThreads << bucket_shift_of(n_keys)) + kThreads;
+    const size_t need = P_pad * 4 + n_cnt * 4 + P_pad * 4;
+    return need > segments_lds_bytes(P) ? need : segments_lds_bytes(P);
+}
+
+hipError_t launch_segments(const SegParams &p_in, hipStream_t s)
+{
+    SegParams p = p_in;
+    // short segments on average and counters that fit LDS beside the radix path's static
+    // arrays: bucket path
+    constexpr size_t kBucketLdsMax = 140 * 1024;
+    const unsigned n_keys = (unsigned)p.n_adapters * (unsigned)p.n_experts;
+    if ((int64_t)p.P < 64 * (int64_t)n_keys && n_keys <= 0x10000u &&
+        bucket_lds_bytes(p.P, n_keys) <= kBucketLdsMax) {
+        p.bucket_shift = bucket_shift_of(n_keys);
+        const size_t dyn = bucket_lds_bytes(p.P, n_keys);
+        static hipError_t attr = hipFuncSetAttribute(
+            reinterpret_cast<const void *>(segments_bucket_kernel),
+            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kBucketLdsMax);
+        if (attr != hipSuccess) return attr;
+        hipLaunchKernelGGL(segments_bucket_kernel, dim3(1), dim3(kThreads), dyn, s, p);
+        return hipGetLastError();
+    }
     const size_t dyn = segments_lds_bytes(p.P);
     if (dyn > 48 * 1024) {
         // ask once for the largest dynamic LDS size this kernel is ever launched with

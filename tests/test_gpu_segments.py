@@ -74,6 +74,41 @@ def test_segments_match_oracle(seed, P, n, E, drop):
     assert torch.equal(seg.perm[:P_act], seg2.perm[:P_act])
 
 
+@pytest.mark.parametrize("P,n,E,hot", [(2000, 64, 1, 0.7), (8192, 128, 8, 0.2), (1024, 256, 1, 1.0),
+                                       (300, 5, 1, 0.95)])
+def test_one_hot_key_among_many(P, n, E, hot):
+    """Many keys but one of them holds a large share of the rows (the counting path hands
+    such a batch over to the radix path inside the kernel)."""
+    rng = np.random.default_rng(P + n)
+    aid = rng.integers(0, n, size=P).astype(np.int32)
+    eid = rng.integers(0, E, size=P).astype(np.int32) if E > 1 else None
+    mask = rng.random(P) < hot
+    aid[mask] = n // 2
+    if eid is not None:
+        eid[mask] = E - 1
+    pool = make_pool(n, E)
+    seg = run_segments(pool, aid, eid)
+    compare(seg, aid, eid, n, E)
+    assert int(seg.status.cpu()[0]) == 0
+
+
+@pytest.mark.parametrize("n,E", [(1, 2), (3, 1), (2, 3), (65536, 1), (257, 255), (1, 65535)])
+def test_key_count_edges(n, E):
+    """Odd and extreme numbers of keys, first and last key occupied."""
+    P = 777
+    rng = np.random.default_rng(n * 7 + E)
+    aid = rng.integers(0, n, size=P).astype(np.int32)
+    eid = rng.integers(0, E, size=P).astype(np.int32) if E > 1 else None
+    aid[:3] = 0
+    aid[3:6] = n - 1
+    if eid is not None:
+        eid[:3] = 0
+        eid[3:6] = E - 1
+    pool = make_pool(n, E)
+    seg = run_segments(pool, aid, eid)
+    compare(seg, aid, eid, n, E)
+
+
 def test_empty_batch_writes_zero_counts():
     pool = make_pool(4, 1)
     seg = L.Segments(1)
