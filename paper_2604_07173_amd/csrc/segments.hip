@@ -35,6 +35,7 @@ struct ScanLds {
     int sum[kWaves];
     int mx[kWaves];
     int mn[kWaves];
+    unsigned two[kWaves][2];
 };
 
 // inclusive prefix sum over the 64 lanes on the cross-lane data path (no LDS round trips):
@@ -70,6 +71,35 @@ __device__ __noinline__ int block_excl_sum(int v, int *total, volatile int *wave
     }
     *total = tot;
     return base + inc - v;
+}
+
+// exclusive prefix sums of two values over the workgroup, plus their totals; one barrier
+__device__ inline void block_excl_sum2(unsigned a, unsigned b, volatile unsigned (*wave_sums)[2],
+                                       unsigned *a_before, unsigned *b_before, unsigned *a_total,
+                                       unsigned *b_total)
+{
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const unsigned ia = wave_incl_sum(a), ib = wave_incl_sum(b);
+    if (lane == 63) {
+        wave_sums[w][0] = ia;
+        wave_sums[w][1] = ib;
+    }
+    __syncthreads();
+    const unsigned ma = wave_sums[lane & (kWaves - 1)][0], mb = wave_sums[lane & (kWaves - 1)][1];
+    unsigned ta = 0, tb = 0, ba = 0, bb = 0;
+#pragma unroll
+    for (int k = 0; k < kWaves; ++k) {
+        const unsigned xa = (unsigned)__builtin_amdgcn_readlane((int)ma, k);
+        const unsigned xb = (unsigned)__builtin_amdgcn_readlane((int)mb, k);
+        ta += xa;
+        tb += xb;
+        ba += k < w ? xa : 0u;
+        bb += k < w ? xb : 0u;
+    }
+    *a_before = ba + ia - a;
+    *b_before = bb + ib - b;
+    *a_total = ta;
+    *b_total = tb;
 }
 
 // three scans with one pair of barriers: exclusive sum of `cnt` (and total), exclusive
@@ -301,7 +331,7 @@ __device__ __forceinline__ void radix_body(const SegParams &p)
                 __builtin_amdgcn_wave_barrier();
             }
             if (val) {
-                dst[pos] = (uint16_t)row;
+                if (p.passes > 1) dst[pos] = (uint16_t)row;       // one pass: nothing reads the order back
                 if (last) p.perm[pos] = (int32_t)row;
             }
         }
@@ -310,6 +340,58 @@ __device__ __forceinline__ void radix_body(const SegParams &p)
             for (int b = tid; b < kWaves * kBins; b += kThreads) (&hist[0][0])[b] = 0;
             __syncthreads();
         }
+    }
+    const int TR = p.tile_rows;       // a power of two
+
+    // ---- one pass (at most 256 keys): the scanned histogram already is the segment table ----
+    if (p.passes == 1) {
+        __shared__ unsigned bin_tile0[kBins];     // first tile of the key (exclusive prefix)
+        __shared__ unsigned bin_seg[kBins];       // segment index of the key
+        const int tr_shift = 31 - __clz(TR);
+        unsigned start = 0, n = 0;
+        if (tid < kBins) {
+            start = hist[0][tid];                                  // wave 0's start = the key's start
+            n = (tid + 1 < kBins ? hist[0][tid + 1] : (unsigned)P_act) - start;
+        }
+        const unsigned my_tiles = (n + TR - 1) >> tr_shift;
+        unsigned seg_before, tile_before, S, n_tiles;
+        block_excl_sum2(n ? 1u : 0u, my_tiles, scan.two, &seg_before, &tile_before, &S, &n_tiles);
+        if (tid < kBins) {
+            bin_tile0[tid] = tile_before;
+            bin_seg[tid] = seg_before;
+            if (n) {
+                p.seg_start[seg_before] = (int32_t)start;
+                p.seg_key[seg_before] = tid;
+            }
+        }
+        __syncthreads();
+        // tiles, one per thread and turn: the key of tile ti is the last one whose first tile
+        // is not beyond ti (an empty key shares its first tile with the next key, which wins)
+#pragma unroll 1
+        for (unsigned ti = tid; ti < n_tiles; ti += kThreads) {
+            int key = 0;
+#pragma unroll
+            for (int step = kBins / 2; step > 0; step >>= 1)
+                if (bin_tile0[key + step] <= ti) key += step;
+            const unsigned kstart = hist[0][key];
+            const unsigned kend = key + 1 < kBins ? hist[0][key + 1] : (unsigned)P_act;
+            const unsigned r = (ti - bin_tile0[key]) << tr_shift;
+            lora_tile t;
+            t.key = key;
+            t.row0 = (int32_t)(kstart + r);
+            t.n_rows = (int32_t)min((unsigned)TR, kend - kstart - r);
+            t.seg = (int32_t)bin_seg[key];
+            p.tiles[ti] = t;
+        }
+        if (tid == 0) {
+            p.seg_start[S] = P_act;
+            p.counts[0] = (int32_t)S;
+            p.counts[1] = P_act;
+            p.counts[2] = (int32_t)n_tiles;
+            p.counts[3] = 0;
+            p.status[0] = status_bits;
+        }
+        return;
     }
     const uint16_t *sorted = order[(p.passes - 1) & 1];
 
@@ -333,7 +415,6 @@ __device__ __forceinline__ void radix_body(const SegParams &p)
     next_after = min(next_after, P_act);
 
     // ---- segment records and tile starts -------------------------------------------------
-    const int TR = p.tile_rows;       // a power of two
     unsigned T = 0;                   // tile starts among my positions
     {
         int sidx = seg_before;
@@ -399,35 +480,6 @@ __global__ __launch_bounds__(kThreads) void segments_kernel(SegParams p)
 // thread-owned range so that the threads' range walks hit different banks.
 constexpr int kMaxBucket = 256;
 typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
-
-// exclusive prefix sums of two values over the workgroup, plus their totals; one barrier
-__device__ inline void block_excl_sum2(unsigned a, unsigned b, volatile unsigned (*wave_sums)[2],
-                                       unsigned *a_before, unsigned *b_before, unsigned *a_total,
-                                       unsigned *b_total)
-{
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    const unsigned ia = wave_incl_sum(a), ib = wave_incl_sum(b);
-    if (lane == 63) {
-        wave_sums[w][0] = ia;
-        wave_sums[w][1] = ib;
-    }
-    __syncthreads();
-    const unsigned ma = wave_sums[lane & (kWaves - 1)][0], mb = wave_sums[lane & (kWaves - 1)][1];
-    unsigned ta = 0, tb = 0, ba = 0, bb = 0;
-#pragma unroll
-    for (int k = 0; k < kWaves; ++k) {
-        const unsigned xa = (unsigned)__builtin_amdgcn_readlane((int)ma, k);
-        const unsigned xb = (unsigned)__builtin_amdgcn_readlane((int)mb, k);
-        ta += xa;
-        tb += xb;
-        ba += k < w ? xa : 0u;
-        bb += k < w ? xb : 0u;
-    }
-    *a_before = ba + ia - a;
-    *b_before = bb + ib - b;
-    *a_total = ta;
-    *b_total = tb;
-}
 
 __global__ __launch_bounds__(kThreads) void segments_bucket_kernel(SegParams p)
 {
