@@ -109,6 +109,28 @@ def test_key_count_edges(n, E):
     compare(seg, aid, eid, n, E)
 
 
+def test_random_shapes_and_skews():
+    """Sixty random batches: sizes, key counts, share of rows without adapter and skew of
+    the adapter popularity all drawn at random; every one bit-exact against the oracle."""
+    rng = np.random.default_rng(20240607)
+    for case in range(60):
+        P = int(rng.choice([1, 2, 63, 64, 65, 127, 500, 1023, 1024, 2049, 4096, 7000, 16384]))
+        n = int(rng.choice([1, 2, 5, 16, 64, 255, 256, 257, 1000, 4096]))
+        E = int(rng.choice([1, 1, 2, 8, 16, 60, 128]))
+        if n * E > 2 ** 24:
+            E = 1
+        power = float(rng.choice([1.0, 2.0, 4.0]))          # 1 = uniform, larger = more skew
+        aid = np.minimum((n * rng.random(P) ** power).astype(np.int32), n - 1)
+        aid[rng.random(P) < float(rng.choice([0.0, 0.05, 0.5]))] = -1
+        eid = rng.integers(0, E, size=P).astype(np.int32) if E > 1 else None
+        pool = make_pool(n, E)
+        seg = run_segments(pool, aid, eid)
+        try:
+            compare(seg, aid, eid, n, E)
+        except AssertionError as err:
+            raise AssertionError(f"case {case}: P={P} n={n} E={E} power={power}") from err
+
+
 def test_empty_batch_writes_zero_counts():
     pool = make_pool(4, 1)
     seg = L.Segments(1)
