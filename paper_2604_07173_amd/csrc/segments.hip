@@ -1,24 +1,29 @@
 // Segment builder: stable counting sort of the batch rows by key = adapter * E + expert,
-// then segment boundaries and row tiles.  One workgroup of 1024 threads does the whole job
-// out of LDS (a batch has at most 16384 rows and the result feeds kernels that run right
-// after it, so latency matters, not bandwidth; gfx950 has 160 KiB of LDS per workgroup).
-// Global memory is only read for the ids and only written for the results.
+// then segment boundaries and row tiles (App. A.2.2: rows of one adapter are aggregated so its
+// weights are read once; Sec. 2.3: per (adapter, expert) in MoE layers).  One workgroup of
+// 1024 threads does the whole job out of LDS (a batch has at most 16384 rows and the result
+// feeds kernels that run right after it, so latency matters, not bandwidth; gfx950 has
+// 160 KiB of LDS per workgroup).  Global memory is only read for the ids and only written for
+// the results.  One CU issues one wave instruction per four cycles and SIMD, so the time of
+// either path below is essentially its instruction count.
 //
-// LDS holds key[row] for the whole batch and two 16-bit row-index arrays that the radix
-// passes (8 key bits each, least significant first) ping-pong between; the keys never move.
+// Two paths with identical results (rows ordered by key, original order inside a key):
 //
-// Stability without order-defining atomics: in every pass wave w owns the contiguous
-// positions [w*CH, (w+1)*CH) of the current order; it walks them 64 at a time in order,
-// ranks equal digits inside a group of 64 by lane order (ballot match) and keeps a running
-// per-digit count of its own (LDS adds whose only effect is a sum, so their order does not
-// matter); an exclusive scan over (digit, wave) in digit-major order turns the counts into
-// start positions.  Equal keys therefore keep their original order and the output is
-// unique, hence bit-identical run to run.
+// * Radix path (segments_kernel; long segments, or key spaces too large for LDS counters).
+//   LDS holds key[row] for the whole batch and two 16-bit row-index arrays that the radix
+//   passes (8 key bits each, least significant first) ping-pong between; the keys never move.
+//   Stability without order-defining atomics: in every pass wave w owns the contiguous
+//   positions [w*CH, (w+1)*CH) of the current order; it walks them 64 at a time in order,
+//   ranks equal digits inside a group of 64 by lane order (ballot match) and keeps a running
+//   per-digit count of its own (LDS adds whose only effect is a sum, so their order does not
+//   matter); an exclusive scan over (digit, wave) in digit-major order turns the counts into
+//   start positions.  With a single pass (at most 256 keys) the scanned histogram already is
+//   the segment table.  Otherwise thread t owns `items` consecutive sorted positions and keeps
+//   the boundary flags of its positions as a bit mask; three block scans (count of
+//   boundaries, last boundary before, first boundary after) give every position its segment
+//   index, start and end without reading anything back from global memory.
 //
-// Boundaries and tiles: thread t owns `items` consecutive sorted positions and keeps the
-// boundary flags of its positions as a bit mask; three block scans (count of boundaries,
-// last boundary before, first boundary after) give every position its segment index, start
-// and end without reading anything back from global memory.
+// * Counting path (segments_bucket_kernel; many short segments): described at the kernel.
 #include "lora_internal.h"
 
 namespace lora {
