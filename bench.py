@@ -34,7 +34,8 @@ def parse_args():
     ap.add_argument("--seed", type=int, default=1234)
     ap.add_argument("--hot", action="store_true", help="reuse one layer (weights warm in cache)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--all", action="store_true", help="also measure the other workloads (extra field)")
+    ap.add_argument("--all", action="store_true",
+                    help="also measure the other workloads and the layer-wise adapter load (extra field)")
     ap.add_argument("--launch", choices=["graph", "stream"], default="graph",
                     help="how the timed steps are launched: one HIP graph holding all K steps "
                          "(as a serving engine captures a decode iteration), or plain stream launches")
@@ -288,6 +289,81 @@ def cpu_baseline(w, b, ws):
                        f"{len(w.projs)} projections), median of {len(times)} runs, {t:.3f} s each")
 
 
+def measure_adapter_load(args):
+    """Sec. 5.3, layer-wise loading: one Mixtral-shaped adapter (8 experts, gate/up/down,
+    rank 16) goes from pinned host memory into its pool slot layer by layer on a loading
+    stream, alone and while the decode layer call keeps running on the compute stream.
+    The slot is re-loaded with the bytes it already holds, so the concurrent steps read
+    the same values throughout."""
+    import numpy as np
+    import torch
+
+    import paper_2604_07173_amd as L
+    import workloads as W
+    from paper_2604_07173_amd.harness import DeviceBatch, DevicePool, LayerRunner
+
+    w = W.WORKLOADS["mixtral_moe_decode"]
+    n_layers = args.layers or DEFAULT_LAYERS.get("mixtral_moe_decode", 8)
+    b = W.make_batch(w, args.seed, y_mode="normal")
+    ws = W.make_weights(w, args.seed, n_layers=n_layers)
+    dp = DevicePool(ws, b.scale)
+    db = DeviceBatch(b)
+    run = LayerRunner(dp, db)
+    slot = w.n_adapters - 1
+    window = L.lora_pool_adapter_layer_bytes(dp.pool, slot)
+    win = window // 2
+    host = torch.from_numpy(np.concatenate(
+        [ws.bank[int(ws.window[slot, l]):int(ws.window[slot, l]) + win].view(np.int16)
+         for l in range(n_layers)])).pin_memory()
+    staging = torch.empty(win, dtype=torch.int16, device="cuda")
+    load_stream = torch.cuda.Stream()
+
+    def load_and_poll():
+        t0 = time.perf_counter()
+        L.lora_pool_load_adapter_async(dp.pool, slot, host, staging, load_stream=load_stream)
+        while not L.lora_pool_layer_ready(dp.pool, slot, 0):
+            pass
+        t_first = time.perf_counter()
+        while not L.lora_pool_layer_ready(dp.pool, slot, n_layers - 1):
+            pass
+        return t_first - t0, time.perf_counter() - t0
+
+    def steps(n):
+        for it in range(n):
+            run.step(it % n_layers)
+
+    for _ in range(2):
+        load_and_poll()
+    torch.cuda.synchronize()
+    alone = sorted(load_and_poll() for _ in range(7))[3]
+    # compute alone, then compute with a load in flight
+    n = 4 * max(1, int(alone[1] / 110e-6))
+    steps(20)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    steps(n)
+    e1.record()
+    torch.cuda.synchronize()
+    step_alone = e0.elapsed_time(e1) / n
+    e0.record()
+    steps(n)
+    e1.record()
+    under = load_and_poll()
+    torch.cuda.synchronize()
+    step_loading = e0.elapsed_time(e1) / n
+    total = window * n_layers
+    return {"adapter_bytes": total, "layers": n_layers, "layer_bytes": window,
+            "first_layer_ready_ms": round(alone[0] * 1e3, 3), "all_layers_ready_ms": round(alone[1] * 1e3, 3),
+            "h2d_gbs": round(total / alone[1] / 1e9, 1),
+            "with_decode_running": {"first_layer_ready_ms": round(under[0] * 1e3, 3),
+                                    "all_layers_ready_ms": round(under[1] * 1e3, 3),
+                                    "h2d_gbs": round(total / under[1] / 1e9, 1),
+                                    "decode_ms_per_step_alone": round(step_alone, 5),
+                                    "decode_ms_per_step_while_loading": round(step_loading, 5),
+                                    "steps_enqueued": n}}
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -351,6 +427,7 @@ def main():
                            "algorithmic_bytes_per_step": r["algorithmic_bytes"],
                            "phases": {k: {"us": round(v["us"], 2), "GB/s": round(v["gbs"], 1)}
                                       for k, v in r["phases"].items()}}
+        extra["adapter_load_mixtral"] = measure_adapter_load(args)
         out["extra"] = extra
     print(json.dumps(out))
     return 0

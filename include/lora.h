@@ -116,6 +116,33 @@ int lora_pool_load_unit(lora_pool *pool, int adapter, int layer, int expert, int
 int lora_pool_load_adapter_layer(lora_pool *pool, int adapter, int layer, const void *src,
                                  void *stream);
 
+/*
+ * Layer-wise loading of a whole adapter into its slot of the pool (Sec. 5.3: transfer and
+ * computation are pipelined at layer granularity, so the first layer can compute as soon
+ * as its weights have arrived while later layers are still on their way).
+ *
+ * lora_pool_adapter_layer_bytes: bytes of one (adapter, layer) source window, laid out as
+ *   lora_pool_load_adapter_layer expects it; 0 on a bad argument.
+ * lora_pool_load_adapter_async: host_src = pinned host memory holding the n_layers windows
+ *   of the adapter back to back, layer 0 first.  For every layer in order, on load_stream:
+ *   copy the window to `staging` (device, 16-byte aligned, at least one window), repack it
+ *   into the pool, record the layer's ready event.  Returns after enqueueing; host_src and
+ *   staging must stay untouched until the last layer is ready.  The slot keeps the rank and
+ *   scale it was registered with.  Replacing an adapter that launched work may still read
+ *   is the caller's to order (make load_stream wait for that work first).
+ * lora_pool_wait_layer: make `stream` wait (on the device, without blocking the host) until
+ *   the latest load of (adapter, layer) enqueued before this call has landed; a no-op for a
+ *   layer that was never loaded asynchronously.
+ * lora_pool_layer_ready: 1 if that load has completed (or none was ever enqueued), 0 if it
+ *   is still in flight, a negative lora_status on error.  Never blocks.
+ * These four calls and lora_pool_destroy on one pool must not race with each other.
+ */
+size_t lora_pool_adapter_layer_bytes(const lora_pool *pool, int adapter);
+int lora_pool_load_adapter_async(lora_pool *pool, int adapter, const void *host_src,
+                                 void *staging, size_t staging_bytes, void *load_stream);
+int lora_pool_wait_layer(const lora_pool *pool, int adapter, int layer, void *stream);
+int lora_pool_layer_ready(const lora_pool *pool, int adapter, int layer);
+
 /* Inverse of the repacking: write one unit's projection back as row-major bf16
  * A[h_in][rank] and B[rank][h_out] (pool rank, zero padding included). */
 int lora_pool_read_unit(const lora_pool *pool, int adapter, int layer, int expert, int proj,

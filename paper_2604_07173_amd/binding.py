@@ -17,7 +17,8 @@ LORA_MAX_ROWS = 1 << 14
 
 EXPORTED_SYMBOLS = [
     "lora_strerror", "lora_last_hip_error", "lora_pool_bytes", "lora_register_pool",
-    "lora_pool_load_unit", "lora_pool_load_adapter_layer", "lora_pool_read_unit",
+    "lora_pool_load_unit", "lora_pool_load_adapter_layer", "lora_pool_adapter_layer_bytes",
+    "lora_pool_load_adapter_async", "lora_pool_wait_layer", "lora_pool_layer_ready", "lora_pool_read_unit",
     "lora_pool_unit_layout", "lora_pool_device_table", "lora_pool_destroy",
     "lora_segments_ws_bytes", "lora_build_segments", "lora_v_bytes", "lora_shrink",
     "lora_expand", "lora_apply", "lora_group_ws_bytes", "lora_apply_group", "lora_moe_ws_bytes", "lora_moe_apply", "lora_moe_shrink", "lora_moe_expand",
@@ -83,6 +84,14 @@ def load_library():
     lib.lora_pool_load_unit.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp]
     lib.lora_pool_load_adapter_layer.restype = i32
     lib.lora_pool_load_adapter_layer.argtypes = [vp, i32, i32, vp, vp]
+    lib.lora_pool_adapter_layer_bytes.restype = C.c_size_t
+    lib.lora_pool_adapter_layer_bytes.argtypes = [vp, i32]
+    lib.lora_pool_load_adapter_async.restype = i32
+    lib.lora_pool_load_adapter_async.argtypes = [vp, i32, vp, vp, C.c_size_t, vp]
+    lib.lora_pool_wait_layer.restype = i32
+    lib.lora_pool_wait_layer.argtypes = [vp, i32, i32, vp]
+    lib.lora_pool_layer_ready.restype = i32
+    lib.lora_pool_layer_ready.argtypes = [vp, i32, i32]
     lib.lora_pool_read_unit.restype = i32
     lib.lora_pool_read_unit.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp]
     lib.lora_pool_unit_layout.restype = i32
@@ -240,6 +249,30 @@ def lora_pool_load_adapter_layer(pool, adapter, layer, src, stream=None):
     _check(load_library().lora_pool_load_adapter_layer(_h(pool), adapter, layer, _addr(src),
                                                        _stream(stream)),
            "lora_pool_load_adapter_layer")
+
+
+def lora_pool_adapter_layer_bytes(pool, adapter) -> int:
+    return int(load_library().lora_pool_adapter_layer_bytes(_h(pool), adapter))
+
+
+def lora_pool_load_adapter_async(pool, adapter, host_src, staging, load_stream=None):
+    """host_src: pinned host tensor (all layers back to back); staging: device tensor."""
+    _check(load_library().lora_pool_load_adapter_async(
+        _h(pool), adapter, _addr(host_src), _addr(staging),
+        staging.numel() * staging.element_size(), _stream(load_stream)),
+        "lora_pool_load_adapter_async")
+
+
+def lora_pool_wait_layer(pool, adapter, layer, stream=None):
+    _check(load_library().lora_pool_wait_layer(_h(pool), adapter, layer, _stream(stream)),
+           "lora_pool_wait_layer")
+
+
+def lora_pool_layer_ready(pool, adapter, layer) -> bool:
+    rc = load_library().lora_pool_layer_ready(_h(pool), adapter, layer)
+    if rc < 0:
+        _check(rc, "lora_pool_layer_ready")
+    return rc == 1
 
 
 def lora_pool_read_unit(pool, adapter, layer, expert, proj, A_out, B_out, stream=None):

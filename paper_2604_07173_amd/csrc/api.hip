@@ -72,6 +72,7 @@ struct lora_pool {
     size_t A_off[LORA_MAX_PROJ], A_bytes[LORA_MAX_PROJ];
     size_t B_off[LORA_MAX_PROJ], B_bytes[LORA_MAX_PROJ];
     std::vector<Unit> table;              // host mirror of the device table
+    std::vector<hipEvent_t> ready;        // [adapter][layer], created at the first async load
 
     size_t unit_base(int layer, int adapter, int expert) const
     {
@@ -576,6 +577,75 @@ int lora_pool_load_adapter_layer(lora_pool *pool, int adapter, int layer, const 
     return LORA_OK;
 }
 
+size_t lora_pool_adapter_layer_bytes(const lora_pool *pool, int adapter)
+{
+    if (check_pool(pool) != LORA_OK || check_unit(pool, adapter, 0, 0, 0) != LORA_OK) return 0;
+    const int r = pool->arank[adapter];
+    size_t elems = 0;
+    for (int j = 0; j < pool->d.n_proj; ++j)
+        elems += ((size_t)pool->d.proj[j].h_in + pool->d.proj[j].h_out) * r;
+    return elems * pool->d.n_experts * sizeof(uint16_t);
+}
+
+int lora_pool_load_adapter_async(lora_pool *pool, int adapter, const void *host_src, void *staging,
+                                 size_t staging_bytes, void *load_stream)
+{
+    int rc = check_pool(pool);
+    if (rc != LORA_OK) return rc;
+    rc = check_unit(pool, adapter, 0, 0, 0);
+    if (rc != LORA_OK) return rc;
+    if (!host_src || !staging) return LORA_ERR_INVALID_ARG;
+    if (!aligned(host_src, 2) || !aligned(staging, 16)) return LORA_ERR_MISALIGNED;
+    const size_t window = lora_pool_adapter_layer_bytes(pool, adapter);
+    if (staging_bytes < window) return LORA_ERR_BUFFER_TOO_SMALL;
+    hipStream_t st = static_cast<hipStream_t>(load_stream);
+    const int n_layers = pool->d.n_layers;
+    if (pool->ready.empty()) pool->ready.assign((size_t)pool->d.n_adapters * n_layers, nullptr);
+    for (int l = 0; l < n_layers; ++l) {
+        hipEvent_t &ev = pool->ready[(size_t)adapter * n_layers + l];
+        if (!ev) LORA_HIP(hipEventCreateWithFlags(&ev, hipEventDisableTiming));
+        // one staging window: the copy of layer l+1 is ordered behind the repack of layer l
+        LORA_HIP(hipMemcpyAsync(staging, static_cast<const char *>(host_src) + (size_t)l * window, window,
+                                hipMemcpyHostToDevice, st));
+        rc = lora_pool_load_adapter_layer(pool, adapter, l, staging, load_stream);
+        if (rc != LORA_OK) return rc;
+        LORA_HIP(hipEventRecord(ev, st));
+    }
+    return LORA_OK;
+}
+
+int lora_pool_wait_layer(const lora_pool *pool, int adapter, int layer, void *stream)
+{
+    int rc = check_pool(pool);
+    if (rc != LORA_OK) return rc;
+    rc = check_unit(pool, adapter, layer, 0, 0);
+    if (rc != LORA_OK) return rc;
+    if (pool->ready.empty()) return LORA_OK;
+    hipEvent_t ev = pool->ready[(size_t)adapter * pool->d.n_layers + layer];
+    if (!ev) return LORA_OK;
+    LORA_HIP(hipStreamWaitEvent(static_cast<hipStream_t>(stream), ev, 0));
+    return LORA_OK;
+}
+
+int lora_pool_layer_ready(const lora_pool *pool, int adapter, int layer)
+{
+    int rc = check_pool(pool);
+    if (rc != LORA_OK) return rc;
+    rc = check_unit(pool, adapter, layer, 0, 0);
+    if (rc != LORA_OK) return rc;
+    if (pool->ready.empty()) return 1;
+    hipEvent_t ev = pool->ready[(size_t)adapter * pool->d.n_layers + layer];
+    if (!ev) return 1;
+    const hipError_t e = hipEventQuery(ev);
+    if (e == hipSuccess) return 1;
+    if (e == hipErrorNotReady) {
+        (void)hipGetLastError();          // "not ready" is an answer, not an error to leave behind
+        return 0;
+    }
+    LORA_HIP(e);
+    return LORA_ERR_HIP;
+}
+
 int lora_pool_read_unit(const lora_pool *pool, int adapter, int layer, int expert, int proj,
                         void *A_out, void *B_out, void *stream)
 {
@@ -632,6 +702,8 @@ int lora_pool_destroy(lora_pool *pool)
     int rc = check_pool(pool);
     if (rc != LORA_OK) return rc;
     pool->magic = 0;
+    for (hipEvent_t e : pool->ready)
+        if (e) (void)hipEventDestroy(e);
     delete pool;
     return LORA_OK;
 }

@@ -156,3 +156,117 @@ def test_layerwise_loading_on_a_second_stream_overlaps_with_compute():
     torch.cuda.synchronize()
     for l in range(n_layers):
         check_accumulate(bits_from_dev(ys[l]), oracle_projection(b, ws, l, 0), f"layer {l}")
+
+
+def _async_case(n_layers=5, n_experts=3, seed=83):
+    w = W.Workload("t", "moe", 4, n_experts, 2, 16,
+                   (W.Proj("up", 136, 264, "x"), W.Proj("down", 264, 136, "h")), 48, "uniform", 0.0)
+    b = W.make_batch(w, seed, y_mode="normal", hetero_scale=True)
+    ws = W.make_weights(w, seed, n_layers=n_layers, bank_elems=1 << 21)
+    desc = L.PoolDesc(w.n_adapters, n_layers, n_experts, [(136, 264), (264, 136)], 16,
+                      scale=[float(s) for s in b.scale])
+    slab = torch.zeros(L.lora_pool_bytes(desc), dtype=torch.uint8, device="cuda")
+    pool = L.lora_register_pool(desc, slab)
+    torch.cuda.synchronize()
+    return w, b, ws, pool, slab
+
+
+def test_async_adapter_load_layer_by_layer_matches_oracle():
+    """Sec. 5.3 through the library's own calls: every adapter is loaded from pinned host
+    memory on a loading stream, layer after layer; the compute stream waits for a layer of
+    all adapters, then runs that layer.  Every layer's output must match the oracle."""
+    from gpu_common import check_accumulate, oracle_projection
+    from paper_2604_07173_amd.harness import DeviceBatch
+
+    n_layers = 5
+    w, b, ws, pool, slab = _async_case(n_layers)
+    window = L.lora_pool_adapter_layer_bytes(pool, 0)
+    assert window == w.n_experts * sum((p.h_in + p.h_out) * 16 for p in w.projs) * 2
+    win = window // 2
+    host = []
+    for a in range(w.n_adapters):
+        rows = [ws.bank[int(ws.window[a, l]):int(ws.window[a, l]) + win].view(np.int16) for l in range(n_layers)]
+        host.append(torch.from_numpy(np.concatenate(rows)).pin_memory())
+    staging = [torch.empty(win, dtype=torch.int16, device="cuda") for _ in range(w.n_adapters)]
+    load_stream, compute_stream = torch.cuda.Stream(), torch.cuda.Stream()
+
+    db = DeviceBatch(b)
+    v = torch.empty(max(L.lora_v_bytes(pool, 0, db.P), 256) // 4, dtype=torch.float32, device="cuda")
+    assert L.lora_pool_layer_ready(pool, 0, 0)              # nothing enqueued yet
+    for a in range(w.n_adapters):
+        L.lora_pool_load_adapter_async(pool, a, host[a], staging[a], load_stream=load_stream)
+    ys = []
+    with torch.cuda.stream(compute_stream):
+        L.lora_build_segments(pool, db.adapter_id, db.expert_id, db.P, db.seg, stream=compute_stream)
+        for l in range(n_layers):
+            for a in range(w.n_adapters):
+                L.lora_pool_wait_layer(pool, a, l, stream=compute_stream)
+            y = to_dev(b.y_in["up"])
+            x = db.inputs["x"]
+            L.lora_apply(pool, l, 0, x, x.shape[1], db.token_of_pair, db.seg, y, y.shape[1], v,
+                         stream=compute_stream)
+            ys.append(y)
+    torch.cuda.synchronize()
+    assert all(L.lora_pool_layer_ready(pool, a, l) for a in range(w.n_adapters) for l in range(n_layers))
+    for l in range(n_layers):
+        check_accumulate(bits_from_dev(ys[l]), oracle_projection(b, ws, l, 0), f"layer {l}")
+    # the repacked units read back bit-exact
+    p0 = w.projs[0]
+    A_out = torch.empty((p0.h_in, 16), dtype=torch.int16, device="cuda")
+    B_out = torch.empty((16, p0.h_out), dtype=torch.int16, device="cuda")
+    L.lora_pool_read_unit(pool, 2, n_layers - 1, 1, 0, A_out, B_out)
+    torch.cuda.synchronize()
+    A, B = ws.unit_arrays(2, n_layers - 1, 1, 0)
+    assert np.array_equal(bits_from_dev(A_out), A) and np.array_equal(bits_from_dev(B_out), B)
+
+
+def test_async_load_replaces_an_adapter_in_its_slot():
+    """A second load into the same slot (eviction) ordered behind the work that used the
+    first: results switch from the first adapter's weights to the second's."""
+    from gpu_common import check_accumulate, oracle_projection
+    from paper_2604_07173_amd.harness import DeviceBatch
+
+    n_layers = 2
+    w, b, ws, pool, slab = _async_case(n_layers, seed=85)
+    ws2 = W.make_weights(w, 86, n_layers=n_layers, bank_elems=1 << 21)
+    win = L.lora_pool_adapter_layer_bytes(pool, 0) // 2
+
+    def pinned(src, a):
+        rows = [src.bank[int(src.window[a, l]):int(src.window[a, l]) + win].view(np.int16) for l in range(n_layers)]
+        return torch.from_numpy(np.concatenate(rows)).pin_memory()
+
+    staging = torch.empty(win, dtype=torch.int16, device="cuda")
+    stream = torch.cuda.Stream()
+    db = DeviceBatch(b)
+    v = torch.empty(max(L.lora_v_bytes(pool, 0, db.P), 256) // 4, dtype=torch.float32, device="cuda")
+    keep = []
+    for src in (ws, ws2):
+        hosts = [pinned(src, a) for a in range(w.n_adapters)]
+        keep.append(hosts)
+        with torch.cuda.stream(stream):
+            for a in range(w.n_adapters):           # one staging window, one stream: loads are ordered
+                L.lora_pool_load_adapter_async(pool, a, hosts[a], staging, load_stream=stream)
+            L.lora_build_segments(pool, db.adapter_id, db.expert_id, db.P, db.seg, stream=stream)
+            y = to_dev(b.y_in["up"])
+            x = db.inputs["x"]
+            L.lora_apply(pool, 1, 0, x, x.shape[1], db.token_of_pair, db.seg, y, y.shape[1], v, stream=stream)
+        torch.cuda.synchronize()
+        check_accumulate(bits_from_dev(y), oracle_projection(b, src, 1, 0), "slot contents")
+
+
+def test_async_load_argument_errors():
+    w, b, ws, pool, slab = _async_case(2)
+    win = L.lora_pool_adapter_layer_bytes(pool, 0) // 2
+    host = torch.zeros(2 * win, dtype=torch.int16).pin_memory()
+    small = torch.empty(win - 8, dtype=torch.int16, device="cuda")
+    ok = torch.empty(win, dtype=torch.int16, device="cuda")
+    with pytest.raises(L.LoraError):
+        L.lora_pool_load_adapter_async(pool, 0, host, small)
+    with pytest.raises(L.LoraError):
+        L.lora_pool_load_adapter_async(pool, 99, host, ok)
+    with pytest.raises(L.LoraError):
+        L.lora_pool_wait_layer(pool, 0, 7)
+    with pytest.raises(L.LoraError):
+        L.lora_pool_layer_ready(pool, -1, 0)
+    assert L.lora_pool_adapter_layer_bytes(pool, 99) == 0
+    torch.cuda.synchronize()
