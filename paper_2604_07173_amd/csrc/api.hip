@@ -349,7 +349,12 @@ int do_expand(const lora_pool *pool, int layer, const Group &g, const lora_segme
         }
         for (int j = g.n; j < kMaxFused; ++j) ep.slice0[j + 1] = ep.slice0[g.n];
         ep.waves = 4;
-        const int64_t wave_items = tub * ep.slice0[g.n];
+        // with many rows per (adapter, expert) a segment spans several tiles: let neighbouring
+        // waves take neighbouring tiles, so that they share the segment's B through the L2
+        static const int tile_group = env_int("LORA_DEC_EXPAND_TILE_GROUP", 0, 0, 4);
+        const int64_t n_keys = (int64_t)pool->d.n_adapters * pool->d.n_experts;
+        ep.tile_group = tile_group ? tile_group : (seg->P >= 8 * n_keys ? 2 : 1);
+        const int64_t wave_items = (tub + ep.tile_group - 1) / ep.tile_group * ep.tile_group * ep.slice0[g.n];
         ep.grid = (int)std::min<int64_t>((wave_items + ep.waves - 1) / ep.waves,
                                          (int64_t)cu_count() * per_cu);
         LORA_HIP(launch_expand_decode(ep, st));

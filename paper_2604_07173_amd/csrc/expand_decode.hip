@@ -193,11 +193,19 @@ __global__ __launch_bounds__(256, 2) void expand16_kernel(ExpandParams p,
     const int gw = __builtin_amdgcn_readfirstlane(blockIdx.x * wpb + wave), nw = gridDim.x * wpb;
     const int n_tiles = counts[2];
     const int per_tile = p.slice0[p.n_fused];                     // wave items of one tile
-    const int n_items = n_tiles * per_tile;
+    // Item order: tile_group consecutive items take the same (projection, slice) of
+    // tile_group consecutive tiles, so the waves of a workgroup that work on tiles of one
+    // segment ask for the same B chunk at about the same time and all but one are served by
+    // the L2.  tile_group 1: consecutive items are the slices of one tile.
+    const int G = p.tile_group;
+    const int n_items = (n_tiles + G - 1) / G * G * per_tile;
 
     for (int item = gw; item < n_items; item += nw) {
-        const int tile_ix = item / per_tile;
-        const int rem = item - tile_ix * per_tile;
+        const int grp = item / (per_tile * G);
+        const int in_grp = item - grp * (per_tile * G);
+        const int rem = in_grp / G;
+        const int tile_ix = grp * G + (in_grp - rem * G);
+        if (tile_ix >= n_tiles) continue;
         const int pj = (rem >= p.slice0[1] ? 1 : 0) + (p.n_fused > 2 && rem >= p.slice0[2] ? 1 : 0);
         const int slice = rem - p.slice0[pj];
         const int cps = p.cps[pj];                                // chunks per slice

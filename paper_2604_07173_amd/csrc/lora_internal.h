@@ -108,6 +108,7 @@ struct ExpandParams {
     void *img[kMaxFused];    // long-segment kernel: operand images of the 16-row sub-tiles
     int image_grid;          // long-segment kernel: workgroups of the image launch
     int waves;               // waves per workgroup
+    int tile_group;          // decode kernel: consecutive wave items walk over this many tiles
     int out_f32;
     int rank;
     int grid;
