@@ -95,6 +95,25 @@ def test_segment_lengths_around_tile_boundaries(tokens):
     check_accumulate(got, res, f"{tokens} rows")
 
 
+@pytest.mark.parametrize("out_f32", [False, True])
+@pytest.mark.parametrize("rank,n,tokens", [(8, 3, 100), (16, 7, 300), (32, 5, 149), (64, 9, 500)])
+def test_segments_of_several_16_row_tiles(rank, n, tokens, out_f32):
+    """8 to 63 rows per adapter: still the 16-row-tile kernels, but most segments span two to
+    four tiles (an odd number of tiles in all, ragged last tiles); the expand then hands
+    neighbouring waves the same slice of neighbouring tiles."""
+    w = dense_workload(rank, 264, 648, n=n, tokens=tokens, ids="zipf", alpha=0.8)
+    assert 8 * n <= tokens < 64 * n
+    b, ws, got, (dp, db, run) = run_dense(w, 16 + rank, "normal", out_f32=out_f32, drop=0.1)
+    assert db.seg.c.tile_rows == 16
+    counts = db.seg.counts.cpu().numpy()
+    assert counts[2] > counts[0]                       # more tiles than segments
+    res = oracle_projection(b, ws, 0, 0)
+    if out_f32:
+        np.testing.assert_allclose(got, res.y_out, rtol=0, atol=2e-5 * max(1.0, np.abs(res.y_out).max()))
+    else:
+        check_accumulate(got, res, f"r{rank} n{n} t{tokens}")
+
+
 @pytest.mark.parametrize("rank,h_in", [(8, 200), (8, 64), (16, 200), (32, 104), (64, 72)])
 def test_thousands_of_small_tiles_one_wave_per_tile(rank, h_in):
     """More than 4096 tiles over a short K range: the shrink runs one wave per tile with the
