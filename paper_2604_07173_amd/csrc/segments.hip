@@ -24,6 +24,8 @@
 //   index, start and end without reading anything back from global memory.
 //
 // * Counting path (segments_bucket_kernel; many short segments): described at the kernel.
+#include <cstdlib>
+
 #include "lora_internal.h"
 
 namespace lora {
@@ -682,7 +684,15 @@ hipError_t launch_segments(const SegParams &p_in, hipStream_t s)
     // arrays: bucket path
     constexpr size_t kBucketLdsMax = 140 * 1024;
     const unsigned n_keys = (unsigned)p.n_adapters * (unsigned)p.n_experts;
-    if ((int64_t)p.P < 64 * (int64_t)n_keys && n_keys <= 0x10000u &&
+    // LORA_SEGMENT_PATH=radix forces the radix path (both give the same result)
+    static const bool force_radix = [] {
+        const char *e = getenv("LORA_SEGMENT_PATH");
+        return e && e[0] == 'r';
+    }();
+    // one radix pass (at most 256 keys) is as fast as the counting path and has no bucket
+    // limit: prefer it once there are enough rows per key for long buckets to be likely
+    const bool radix_is_cheap = p.passes == 1 && (int64_t)p.P >= 8 * (int64_t)n_keys;
+    if (!force_radix && !radix_is_cheap && (int64_t)p.P < 64 * (int64_t)n_keys && n_keys <= 0x10000u &&
         bucket_lds_bytes(p.P, n_keys) <= kBucketLdsMax) {
         p.bucket_shift = bucket_shift_of(n_keys);
         const size_t dyn = bucket_lds_bytes(p.P, n_keys);

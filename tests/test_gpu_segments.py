@@ -131,6 +131,46 @@ def test_random_shapes_and_skews():
             raise AssertionError(f"case {case}: P={P} n={n} E={E} power={power}") from err
 
 
+def test_radix_path_forced_by_environment_gives_the_same_segments():
+    """LORA_SEGMENT_PATH=radix is read once per process, so the forced run is a child process;
+    it must print the digest this process computes on the default path."""
+    import hashlib
+    import os
+    import subprocess
+    import sys
+
+    code = (
+        "import numpy as np, torch, hashlib, sys\n"
+        "sys.path.insert(0, 'tests')\n"
+        "import test_gpu_segments as T\n"
+        "print(T.digest_of_cases())\n")
+    env = dict(os.environ, LORA_SEGMENT_PATH="radix")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    out = subprocess.run([sys.executable, "-c", code], cwd=root, env=env, capture_output=True, text=True,
+                         timeout=300)
+    assert out.returncode == 0, out.stderr[-2000:]
+    assert out.stdout.strip().splitlines()[-1] == digest_of_cases()
+
+
+def digest_of_cases():
+    """Digest of the segment arrays of a few batches that take the counting path by default."""
+    import hashlib
+    h = hashlib.sha256()
+    for seed, P, n, E, drop in [(5, 1024, 32, 8, 0.0), (8, 8192, 256, 128, 0.0), (2, 65, 4, 1, 0.3),
+                                (10, 5000, 300, 100, 0.2)]:
+        rng = np.random.default_rng(seed)
+        aid = rng.integers(0, n, size=P).astype(np.int32)
+        aid[rng.random(P) < drop] = -1
+        eid = rng.integers(0, E, size=P).astype(np.int32) if E > 1 else None
+        seg = run_segments(make_pool(n, E), aid, eid)
+        o = compare(seg, aid, eid, n, E)
+        c = seg.counts.cpu().numpy()
+        for t, k in ((seg.perm, c[1]), (seg.seg_start, c[0] + 1), (seg.seg_key, c[0])):
+            h.update(t.cpu().numpy()[:k].tobytes())
+        h.update(seg.tiles.cpu().numpy()[:c[2]].tobytes())
+    return h.hexdigest()
+
+
 def test_empty_batch_writes_zero_counts():
     pool = make_pool(4, 1)
     seg = L.Segments(1)
