@@ -307,6 +307,38 @@ def test_moe_apply_matches_oracle(rank, h, f, E, k, tokens):
                     f"moe delta {p.name}")
 
 
+def test_two_layer_calls_in_flight_on_two_streams():
+    """Two different batches on one pool, issued alternately on two streams without any
+    synchronisation between them: a call's state is only its own segments and workspace, so
+    both must come out exactly as when they run alone."""
+    w = moe_workload(16, 520, 776, E=4, k=2, tokens=300)
+    ws = W.make_weights(w, 23, n_layers=2, bank_elems=1 << 21)
+    batches = [W.make_batch(w, 23 + i, y_mode="normal", no_adapter_frac=0.05) for i in range(2)]
+    dp = DevicePool(ws, batches[0].scale)
+    alone = []
+    for b in batches:
+        db = DeviceBatch(b)
+        LayerRunner(dp, db).step(1)
+        torch.cuda.synchronize()
+        alone.append({k: v.clone() for k, v in db.y.items()})
+    dbs = [DeviceBatch(b) for b in batches]
+    runs = [LayerRunner(dp, db) for db in dbs]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    torch.cuda.synchronize()
+    for rep in range(5):                 # y accumulates, so each repetition first restores the
+        for i in range(2):               # base output, on the call's own stream
+            with torch.cuda.stream(streams[i]):
+                for k, v in batches[i].y_in.items():
+                    dbs[i].y[k].copy_(to_dev(v), non_blocking=True)
+                runs[i].step(1, stream=streams[i])
+    torch.cuda.synchronize()
+    for i in range(2):
+        for k in alone[i]:
+            assert torch.equal(dbs[i].y[k], alone[i][k]), f"batch {i} {k}"
+    res = oracle_projection(batches[1], ws, 1, 2)
+    check_accumulate(bits_from_dev(dbs[1].y["down"]), res, "down of the second batch")
+
+
 def test_results_are_bit_identical_run_to_run():
     w = moe_workload(16, 520, 264, E=4, k=2, tokens=200)
     b = W.make_batch(w, 20, y_mode="normal")
