@@ -7,7 +7,7 @@ application).  Weights, activations, ids and outputs are resident in HBM before 
 region.  The layer index rotates over several layers' worth of pool so that adapter weights
 come from HBM, not from the 256 MB last-level cache, as they do in layer-by-layer decoding.
 
-Prints one JSON line (see README for the fields).
+Prints one JSON line (the README lists the fields).
 """
 from __future__ import annotations
 
