@@ -560,6 +560,9 @@ int lora_pool_load_adapter_layer(lora_pool *pool, int adapter, int layer, const 
         unit_elems += ((int64_t)pool->d.proj[j].h_in + pool->d.proj[j].h_out) * r;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const size_t base = pool->unit_base(layer, adapter, 0);
+    PackLayerParams ps;
+    memset(&ps, 0, sizeof ps);
+    ps.n_jobs = 2 * pool->d.n_proj;
     int64_t off = 0;
     for (int j = 0; j < pool->d.n_proj; ++j) {
         PackParams pp;
@@ -571,14 +574,15 @@ int lora_pool_load_adapter_layer(lora_pool *pool, int adapter, int layer, const 
         pp.h = pool->d.proj[j].h_in;
         pp.rank = pool->d.rank;
         pp.src_rank = r;
-        LORA_HIP(launch_pack_A(pp, st));
+        ps.job[2 * j] = pp;
         off += (int64_t)pool->d.proj[j].h_in * r;
         pp.src = static_cast<const uint16_t *>(src) + off;
         pp.dst = reinterpret_cast<uint16_t *>(pool->slab + base + pool->B_off[j]);
         pp.h = pool->d.proj[j].h_out;
-        LORA_HIP(launch_pack_B(pp, st));
+        ps.job[2 * j + 1] = pp;
         off += (int64_t)pool->d.proj[j].h_out * r;
     }
+    LORA_HIP(launch_pack_layer(ps, st));      // one launch for all projections and experts
     return LORA_OK;
 }
 

@@ -48,6 +48,12 @@ struct PackParams {
     int src_rank;            // rank of the source matrices (<= rank)
 };
 
+// all A and B repacks of one (adapter, layer) in one launch: job 2j = A, 2j+1 = B of projection j
+struct PackLayerParams {
+    PackParams job[2 * LORA_MAX_PROJ];
+    int n_jobs;
+};
+
 struct SegParams {
     const int32_t *adapter_id;
     const int32_t *expert_id;
@@ -116,6 +122,7 @@ struct ExpandParams {
 
 hipError_t launch_pack_A(const PackParams &p, hipStream_t s);
 hipError_t launch_pack_B(const PackParams &p, hipStream_t s);
+hipError_t launch_pack_layer(const PackLayerParams &p, hipStream_t s);
 hipError_t launch_unpack_A(const PackParams &p, hipStream_t s);   // src = packed, dst = row-major
 hipError_t launch_unpack_B(const PackParams &p, hipStream_t s);
 hipError_t launch_segments(const SegParams &p, hipStream_t s);
