@@ -34,6 +34,8 @@ def parse_args():
     ap.add_argument("--seed", type=int, default=1234)
     ap.add_argument("--hot", action="store_true", help="reuse one layer (weights warm in cache)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-two-calls", action="store_true",
+                    help="skip the two-calls-in-flight measurement (kernel traces then hold one stream only)")
     ap.add_argument("--all", action="store_true",
                     help="also measure the other workloads and the layer-wise adapter load (extra field)")
     ap.add_argument("--launch", choices=["graph", "stream"], default="graph",
@@ -163,26 +165,28 @@ def measure(name, args, steps, warmup, with_cpu_baseline):
     # segments and workspace, on a second stream): what a server that takes the calls of two
     # LLM instances at once gets out of the same kernels; the dispatch gaps of one call are
     # filled by the other.  Not the headline: the paper's server runs calls one by one. --------
-    b2 = W.make_batch(w, args.seed + 1, y_mode="normal")
-    db2 = DeviceBatch(b2)
-    run2 = LayerRunner(dp, db2)
-    lanes = [(run, torch.cuda.Stream()), (run2, torch.cuda.Stream())]
+    two_ms_per_step, bytes2 = float("nan"), acct["total"]
+    if not getattr(args, "no_two_calls", False):
+        b2 = W.make_batch(w, args.seed + 1, y_mode="normal")
+        db2 = DeviceBatch(b2)
+        run2 = LayerRunner(dp, db2)
+        lanes = [(run, torch.cuda.Stream()), (run2, torch.cuda.Stream())]
 
-    def two_calls(n):
-        for it in range(n):
-            r, st = lanes[it & 1]
-            with torch.cuda.stream(st):
-                r.step((warmup + it) % n_layers, stream=st)
+        def two_calls(n):
+            for it in range(n):
+                r, st = lanes[it & 1]
+                with torch.cuda.stream(st):
+                    r.step((warmup + it) % n_layers, stream=st)
 
-    two_calls(2 * max(2, warmup // 2))
-    torch.cuda.synchronize()
-    n2 = steps + (steps & 1)
-    t0 = time.perf_counter()
-    two_calls(n2)
-    torch.cuda.synchronize()
-    two_ms_per_step = (time.perf_counter() - t0) * 1e3 / n2
-    bytes2 = W.algorithmic_bytes(w, b2.adapter_id, b2.expert_id)["total"]
-    del lanes, run2, db2
+        two_calls(2 * max(2, warmup // 2))
+        torch.cuda.synchronize()
+        n2 = steps + (steps & 1)
+        t0 = time.perf_counter()
+        two_calls(n2)
+        torch.cuda.synchronize()
+        two_ms_per_step = (time.perf_counter() - t0) * 1e3 / n2
+        bytes2 = W.algorithmic_bytes(w, b2.adapter_id, b2.expert_id)["total"]
+        del lanes, run2, db2
 
     # ---- spread over the steps: an event between consecutive steps (stream launches; the
     # event records add a little to every step, so the median sits above ms_per_step) -------
@@ -438,11 +442,13 @@ def main():
         "phases": {k: {"us": round(v["us"], 2), "GB/s": round(v["gbs"], 1)}
                    for k, v in main_res["phases"].items()},
         "roofline": main_res["roofline"],
-        "two_calls_in_flight": {"ms_per_step": round(main_res["two_calls"]["ms_per_step"], 5),
-                                "tokens_per_s": round(main_res["two_calls"]["tokens_per_s"], 1),
-                                "hbm_frac_of_peak": round(main_res["two_calls"]["hbm_frac_of_peak"], 4),
-                                "note": "two independent layer calls on two streams; not the headline"},
     }
+    if not args.no_two_calls:
+        out["two_calls_in_flight"] = {
+            "ms_per_step": round(main_res["two_calls"]["ms_per_step"], 5),
+            "tokens_per_s": round(main_res["two_calls"]["tokens_per_s"], 1),
+            "hbm_frac_of_peak": round(main_res["two_calls"]["hbm_frac_of_peak"], 4),
+            "note": "two independent layer calls on two streams; not the headline"}
     if "cpu_baseline" in main_res:
         out["cpu_baseline"] = main_res["cpu_baseline"]
     if args.all:
@@ -456,7 +462,8 @@ def main():
                            "hbm_gbs": round(r["step_gbs"], 1),
                            "hbm_frac_of_peak": round(r["step_frac_of_peak"], 4),
                            "algorithmic_bytes_per_step": r["algorithmic_bytes"],
-                           "two_calls_in_flight_ms_per_step": round(r["two_calls"]["ms_per_step"], 5),
+                           "two_calls_in_flight_ms_per_step":
+                               None if args.no_two_calls else round(r["two_calls"]["ms_per_step"], 5),
                            "phases": {k: {"us": round(v["us"], 2), "GB/s": round(v["gbs"], 1)}
                                       for k, v in r["phases"].items()}}
         extra["adapter_load_mixtral"] = measure_adapter_load(args)
