@@ -105,7 +105,7 @@ def measure(name, args, steps, warmup, with_cpu_baseline):
 
     import paper_2604_07173_amd as L
     import workloads as W
-    from paper_2604_07173_amd.harness import DeviceBatch, DevicePool, LayerRunner
+    from harness import DeviceBatch, DevicePool, LayerRunner
 
     w = W.WORKLOADS[name]
     n_layers = 1 if args.hot else (args.layers or DEFAULT_LAYERS.get(name, 4))
@@ -331,7 +331,7 @@ def measure_adapter_load(args):
 
     import paper_2604_07173_amd as L
     import workloads as W
-    from paper_2604_07173_amd.harness import DeviceBatch, DevicePool, LayerRunner
+    from harness import DeviceBatch, DevicePool, LayerRunner
 
     w = W.WORKLOADS["mixtral_moe_decode"]
     n_layers = args.layers or DEFAULT_LAYERS.get("mixtral_moe_decode", 8)

@@ -11,7 +11,7 @@ import torch
 
 import workloads as W
 
-from . import binding as L
+import paper_2604_07173_amd as L
 
 
 def to_dev(a: np.ndarray, device="cuda") -> torch.Tensor:

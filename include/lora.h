@@ -127,9 +127,11 @@ int lora_pool_load_adapter_layer(lora_pool *pool, int adapter, int layer, const 
  *   of the adapter back to back, layer 0 first.  For every layer in order, on load_stream:
  *   copy the window to `staging` (device, 16-byte aligned, at least one window), repack it
  *   into the pool, record the layer's ready event.  Returns after enqueueing; host_src and
- *   staging must stay untouched until the last layer is ready.  The slot keeps the rank and
- *   scale it was registered with.  Replacing an adapter that launched work may still read
- *   is the caller's to order (make load_stream wait for that work first).
+ *   staging must stay untouched until the last layer is ready.  The source windows are read
+ *   with the slot's current rank and the slot keeps its current scale: when the incoming
+ *   adapter differs in either, call lora_pool_set_adapter on load_stream first.  Work that
+ *   was launched earlier may still be reading the slot's old contents; ordering the load
+ *   behind that work is the caller's job (make load_stream wait for it first).
  * lora_pool_wait_layer: make `stream` wait (on the device, without blocking the host) until
  *   the latest load of (adapter, layer) enqueued before this call has landed; a no-op for a
  *   layer that was never loaded asynchronously.
@@ -138,6 +140,16 @@ int lora_pool_load_adapter_layer(lora_pool *pool, int adapter, int layer, const 
  * These four calls and lora_pool_destroy on one pool must not race with each other.
  */
 size_t lora_pool_adapter_layer_bytes(const lora_pool *pool, int adapter);
+
+/*
+ * Give a slot of the pool another rank (1 .. pool rank) and scale, as when the cache of
+ * Sec. 4.2 replaces one resident adapter by another: rewrites the scale and rank of the slot's
+ * table entries of every layer on `stream` (a small kernel, ordered like any other work on that
+ * stream) and makes later loads into the slot read their source with the new rank.  The packed
+ * matrices themselves are left alone; load the new adapter afterwards (loads zero-pad a rank
+ * below the pool rank, which is exact).
+ */
+int lora_pool_set_adapter(lora_pool *pool, int adapter, int rank, float scale, void *stream);
 int lora_pool_load_adapter_async(lora_pool *pool, int adapter, const void *host_src,
                                  void *staging, size_t staging_bytes, void *load_stream);
 int lora_pool_wait_layer(const lora_pool *pool, int adapter, int layer, void *stream);
@@ -187,6 +199,10 @@ typedef struct lora_tile {   /* device record, 16 bytes */
 typedef struct lora_segments {
     int32_t P;               /* host: rows the ids describe; set by lora_build_segments */
     int32_t tile_rows;       /* host: set by lora_build_segments */
+    int32_t n_keys;          /* host: n_adapters * n_experts of the pool the segments were built
+                                for; set by lora_build_segments.  Every call that takes segments
+                                returns LORA_ERR_NOT_REGISTERED for a pool with another key count */
+    int32_t reserved;        /* host: set to 0 by lora_build_segments */
     int32_t *perm;           /* device [P] */
     int32_t *seg_start;      /* device [P + 1] */
     int32_t *seg_key;        /* device [P] */
@@ -226,6 +242,8 @@ size_t lora_v_bytes(const lora_pool *pool, int proj, int P);
 int lora_shrink(const lora_pool *pool, int layer, int proj, const void *x, int64_t ldx,
                 const int32_t *src_row, const lora_segments *seg, float *v, void *stream);
 
+/* v is not const in lora_expand: for batches of long segments the call keeps the bf16 operand
+ * images of the summed, scaled v in the tail of the same workspace. */
 int lora_expand(const lora_pool *pool, int layer, int proj, float *v,
                 const lora_segments *seg, void *y, int64_t ldy, int out_dtype, void *stream);
 

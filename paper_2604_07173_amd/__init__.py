@@ -7,7 +7,8 @@ library every call raises.
 from .binding import (  # noqa: F401
     LoraError, PoolDesc, Pool, Segments, lib_path, load_library,
     lora_pool_bytes, lora_register_pool, lora_pool_load_unit, lora_pool_load_adapter_layer,
-    lora_pool_adapter_layer_bytes, lora_pool_load_adapter_async, lora_pool_wait_layer,
+    lora_pool_adapter_layer_bytes, lora_pool_load_adapter_async, lora_pool_set_adapter,
+    lora_pool_wait_layer,
     lora_pool_layer_ready, lora_pool_read_unit, lora_pool_unit_layout, lora_pool_destroy,
     lora_segments_ws_bytes, lora_build_segments, lora_v_bytes, lora_shrink, lora_expand, lora_apply,
     lora_group_ws_bytes, lora_apply_group,

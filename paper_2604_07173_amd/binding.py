@@ -18,7 +18,7 @@ LORA_MAX_ROWS = 1 << 14
 EXPORTED_SYMBOLS = [
     "lora_strerror", "lora_last_hip_error", "lora_pool_bytes", "lora_register_pool",
     "lora_pool_load_unit", "lora_pool_load_adapter_layer", "lora_pool_adapter_layer_bytes",
-    "lora_pool_load_adapter_async", "lora_pool_wait_layer", "lora_pool_layer_ready", "lora_pool_read_unit",
+    "lora_pool_load_adapter_async", "lora_pool_set_adapter", "lora_pool_wait_layer", "lora_pool_layer_ready", "lora_pool_read_unit",
     "lora_pool_unit_layout", "lora_pool_device_table", "lora_pool_destroy",
     "lora_segments_ws_bytes", "lora_build_segments", "lora_v_bytes", "lora_shrink",
     "lora_expand", "lora_apply", "lora_group_ws_bytes", "lora_apply_group", "lora_moe_ws_bytes", "lora_moe_apply", "lora_moe_shrink", "lora_moe_expand",
@@ -46,7 +46,8 @@ class _PoolDesc(C.Structure):
 
 
 class _Segments(C.Structure):
-    _fields_ = [("P", C.c_int32), ("tile_rows", C.c_int32), ("perm", C.c_void_p),
+    _fields_ = [("P", C.c_int32), ("tile_rows", C.c_int32), ("n_keys", C.c_int32),
+                ("reserved", C.c_int32), ("perm", C.c_void_p),
                 ("seg_start", C.c_void_p), ("seg_key", C.c_void_p), ("tiles", C.c_void_p),
                 ("counts", C.c_void_p), ("status", C.c_void_p)]
 
@@ -88,6 +89,8 @@ def load_library():
     lib.lora_pool_adapter_layer_bytes.argtypes = [vp, i32]
     lib.lora_pool_load_adapter_async.restype = i32
     lib.lora_pool_load_adapter_async.argtypes = [vp, i32, vp, vp, C.c_size_t, vp]
+    lib.lora_pool_set_adapter.restype = i32
+    lib.lora_pool_set_adapter.argtypes = [vp, i32, i32, C.c_float, vp]
     lib.lora_pool_wait_layer.restype = i32
     lib.lora_pool_wait_layer.argtypes = [vp, i32, i32, vp]
     lib.lora_pool_layer_ready.restype = i32
@@ -261,6 +264,11 @@ def lora_pool_load_adapter_async(pool, adapter, host_src, staging, load_stream=N
         _h(pool), adapter, _addr(host_src), _addr(staging),
         staging.numel() * staging.element_size(), _stream(load_stream)),
         "lora_pool_load_adapter_async")
+
+
+def lora_pool_set_adapter(pool, adapter, rank, scale, stream=None):
+    _check(load_library().lora_pool_set_adapter(_h(pool), adapter, rank, float(scale), _stream(stream)),
+           "lora_pool_set_adapter")
 
 
 def lora_pool_wait_layer(pool, adapter, layer, stream=None):

@@ -44,6 +44,21 @@ int env_int(const char *name, int dflt, int lo, int hi)
     return (int)x;
 }
 
+// Work-split constants.  The library as shipped uses the defaults below, so workspace sizes
+// and launch shapes depend only on the pool and the batch; a build with -DLORA_TUNING reads
+// them from the environment instead (for parameter sweeps, never for the installed library).
+int tune_int(const char *name, int dflt, int lo, int hi)
+{
+#ifdef LORA_TUNING
+    return env_int(name, dflt, lo, hi);
+#else
+    (void)name;
+    (void)lo;
+    (void)hi;
+    return dflt;
+#endif
+}
+
 int cu_count()
 {
     static int n = 0;
@@ -176,14 +191,14 @@ KSplit ksplit_of(const lora_pool *p, int proj, int P)
     if (pick_tile_rows(p, P) == kDecodeTileRows) {
         // decode: parts of about kb_target K-blocks, more of them when the batch has so few
         // tiles that the chip would not be filled otherwise, at most max_parts
-        static const int kb_target = env_int("LORA_DEC_KB_PER_PART", 32, 4, 4096);
-        static const int max_parts = env_int("LORA_DEC_MAX_PARTS", 8, 1, kMaxParts);
-        static const int want_wgs = env_int("LORA_DEC_SHRINK_ITEMS", 1024, 1, 1 << 20);
+        static const int kb_target = tune_int("LORA_DEC_KB_PER_PART", 32, 4, 4096);
+        static const int max_parts = tune_int("LORA_DEC_MAX_PARTS", 8, 1, kMaxParts);
+        static const int want_wgs = tune_int("LORA_DEC_SHRINK_ITEMS", 1024, 1, 1 << 20);
         const int64_t tub = std::max<int64_t>(1, tiles_upper_bound(p, P, kDecodeTileRows));
         // thousands of tiles over a short K range: one wave per tile, K not split at all
-        static const int wpt = env_int("LORA_DEC_WAVE_PER_TILE", -1, -1, 1);
-        static const int wpt_tiles = env_int("LORA_DEC_WAVE_PER_TILE_MIN_TILES", 4096, 1, 1 << 20);
-        static const int wpt_k = env_int("LORA_DEC_WAVE_PER_TILE_MAX_K", 4096, 32, 1 << 20);
+        static const int wpt = tune_int("LORA_DEC_WAVE_PER_TILE", -1, -1, 1);
+        static const int wpt_tiles = tune_int("LORA_DEC_WAVE_PER_TILE_MIN_TILES", 4096, 1, 1 << 20);
+        static const int wpt_k = tune_int("LORA_DEC_WAVE_PER_TILE_MAX_K", 4096, 32, 1 << 20);
         if (wpt == 1 || (wpt < 0 && tub >= wpt_tiles && p->d.proj[proj].h_in <= wpt_k)) {
             KSplit k;
             k.kb_per_part = kblocks;
@@ -204,7 +219,7 @@ KSplit ksplit_of(const lora_pool *p, int proj, int P)
     // long segments: work items are groups of tiles; enough K parts to fill the chip
     const int64_t tub = std::max<int64_t>(1, tiles_upper_bound(p, P, kTileRows));
     const int64_t groups = (tub + shrink_long_tiles() - 1) / shrink_long_tiles();
-    static const int target = env_int("LORA_SHRINK_ITEMS", 512, 1, 1 << 20);
+    static const int target = tune_int("LORA_SHRINK_ITEMS", 512, 1, 1 << 20);
     int want = (int)std::min<int64_t>((target + groups - 1) / groups, kMaxParts);
     int by_size = (kblocks + kPartKBlocks - 1) / kPartKBlocks;
     int n = std::max(want, by_size);
@@ -219,10 +234,15 @@ KSplit ksplit_of(const lora_pool *p, int proj, int P)
     return k;
 }
 
-int check_segments(const lora_segments *s)
+// Segments are only meaningful together with the pool they were built for: the keys index that
+// pool's table, and the kernel family and the workspace layout follow from (pool, P).
+int check_segments(const lora_pool *pool, const lora_segments *s)
 {
     if (!s) return LORA_ERR_INVALID_ARG;
     if (s->P < 0 || (s->tile_rows != kTileRows && s->tile_rows != kDecodeTileRows))
+        return LORA_ERR_NOT_REGISTERED;
+    if ((int64_t)s->n_keys != (int64_t)pool->d.n_adapters * pool->d.n_experts ||
+        s->tile_rows != pick_tile_rows(pool, s->P))
         return LORA_ERR_NOT_REGISTERED;
     if (s->P > 0 && (!s->perm || !s->seg_start || !s->seg_key || !s->tiles || !s->counts || !s->status))
         return LORA_ERR_INVALID_ARG;
@@ -266,7 +286,7 @@ int do_shrink(const lora_pool *pool, int layer, const Group &g, const void *x, i
     sp.rank = pool->d.rank;
     const int64_t items = tiles_upper_bound(pool, seg->P, seg->tile_rows) * ks.n_parts;
     if (seg->tile_rows == kDecodeTileRows) {
-        static const int per_cu = env_int("LORA_DEC_SHRINK_WGS_PER_CU", 8, 1, 64);
+        static const int per_cu = tune_int("LORA_DEC_SHRINK_WGS_PER_CU", 8, 1, 64);
         sp.proj0 = g.proj0;
         sp.n_fused = g.n;
         for (int j = 0; j < g.n; ++j) sp.v[j] = g.v[j];
@@ -277,7 +297,7 @@ int do_shrink(const lora_pool *pool, int layer, const Group &g, const void *x, i
         return LORA_OK;
     }
     // 32-row tiles: work items are groups of tiles; at most two projections per launch
-    static const int per_cu = env_int("LORA_SHRINK_WGS_PER_CU", 2, 1, 64);
+    static const int per_cu = tune_int("LORA_SHRINK_WGS_PER_CU", 2, 1, 64);
     const int64_t groups = (tiles_upper_bound(pool, seg->P, seg->tile_rows) + shrink_long_tiles() - 1) /
                            shrink_long_tiles();
     sp.grid = (int)std::min<int64_t>(groups * ks.n_parts, (int64_t)cu_count() * per_cu);
@@ -313,10 +333,10 @@ int do_expand(const lora_pool *pool, int layer, const Group &g, const lora_segme
         // costs a few load latencies), but a small batch must still yield a few thousand items;
         // the grid holds several times more workgroups than are resident, so that the hardware
         // hands out items as waves finish and tiles of different heights balance out.
-        static const int cpi_max = env_int("LORA_DEC_CHUNKS_PER_ITEM", 8, 1, 4096);
-        static const int item_bytes = env_int("LORA_DEC_ITEM_BYTES", 12288, 1024, 1 << 24);
-        static const int want_items = env_int("LORA_DEC_EXPAND_ITEMS", 4096, 1, 1 << 22);
-        static const int per_cu = env_int("LORA_DEC_EXPAND_WGS_PER_CU", 16, 1, 64);
+        static const int cpi_max = tune_int("LORA_DEC_CHUNKS_PER_ITEM", 8, 1, 4096);
+        static const int item_bytes = tune_int("LORA_DEC_ITEM_BYTES", 12288, 1024, 1 << 24);
+        static const int want_items = tune_int("LORA_DEC_EXPAND_ITEMS", 4096, 1, 1 << 22);
+        static const int per_cu = tune_int("LORA_DEC_EXPAND_WGS_PER_CU", 16, 1, 64);
         ep.proj0 = g.proj0;
         ep.n_fused = g.n;
         int64_t chunks_per_tile = 0;
@@ -351,7 +371,7 @@ int do_expand(const lora_pool *pool, int layer, const Group &g, const lora_segme
         ep.waves = 4;
         // with many rows per (adapter, expert) a segment spans several tiles: let neighbouring
         // waves take neighbouring tiles, so that they share the segment's B through the L2
-        static const int tile_group = env_int("LORA_DEC_EXPAND_TILE_GROUP", 0, 0, 4);
+        static const int tile_group = tune_int("LORA_DEC_EXPAND_TILE_GROUP", 0, 0, 4);
         const int64_t n_keys = (int64_t)pool->d.n_adapters * pool->d.n_experts;
         ep.tile_group = tile_group ? tile_group : (seg->P >= 8 * n_keys ? 2 : 1);
         const int64_t wave_items = (tub + ep.tile_group - 1) / ep.tile_group * ep.tile_group * ep.slice0[g.n];
@@ -362,7 +382,7 @@ int do_expand(const lora_pool *pool, int layer, const Group &g, const lora_segme
     }
     // long segments: operand images of the sub-tiles behind the K parts in each projection's
     // slice of the workspace, then wave items = (group of tiles, projection, 128-column chunk)
-    static const int per_cu = env_int("LORA_EXPAND_WGS_PER_CU", 32, 1, 64);
+    static const int per_cu = tune_int("LORA_EXPAND_WGS_PER_CU", 32, 1, 64);
     ep.proj0 = g.proj0;
     ep.n_fused = g.n;
     ep.slice0[0] = 0;
@@ -586,6 +606,28 @@ int lora_pool_load_adapter_layer(lora_pool *pool, int adapter, int layer, const 
     return LORA_OK;
 }
 
+int lora_pool_set_adapter(lora_pool *pool, int adapter, int rank, float scale, void *stream)
+{
+    int rc = check_pool(pool);
+    if (rc != LORA_OK) return rc;
+    rc = check_unit(pool, adapter, 0, 0, 0);
+    if (rc != LORA_OK) return rc;
+    if (rank < 1 || rank > pool->d.rank) return LORA_ERR_UNSUPPORTED_RANK;
+    if (!(scale == scale)) return LORA_ERR_INVALID_ARG;            // NaN
+    const int per_adapter = pool->d.n_experts * pool->d.n_proj;
+    LORA_HIP(launch_set_adapter(reinterpret_cast<Unit *>(pool->slab), pool->d.n_layers, pool->d.n_adapters,
+                                per_adapter, adapter, rank, scale, static_cast<hipStream_t>(stream)));
+    pool->arank[adapter] = rank;
+    pool->scale[adapter] = scale;
+    for (int l = 0; l < pool->d.n_layers; ++l)
+        for (int k = 0; k < per_adapter; ++k) {
+            Unit &u = pool->table[pool->table_index(l, adapter, 0, 0) + k];
+            u.rank = rank;
+            u.scale = scale;
+        }
+    return LORA_OK;
+}
+
 size_t lora_pool_adapter_layer_bytes(const lora_pool *pool, int adapter)
 {
     if (check_pool(pool) != LORA_OK || check_unit(pool, adapter, 0, 0, 0) != LORA_OK) return 0;
@@ -740,6 +782,8 @@ int lora_build_segments(const lora_pool *pool, const int32_t *adapter_id, const 
     }
     seg->P = P;
     seg->tile_rows = pick_tile_rows(pool, P);
+    seg->n_keys = pool->d.n_adapters * pool->d.n_experts;
+    seg->reserved = 0;
     SegParams sp;
     memset(&sp, 0, sizeof sp);
     sp.adapter_id = adapter_id;
@@ -779,7 +823,7 @@ int lora_shrink(const lora_pool *pool, int layer, int proj, const void *x, int64
 {
     int rc = check_pool(pool);
     if (rc != LORA_OK) return rc;
-    rc = check_segments(seg);
+    rc = check_segments(pool, seg);
     if (rc != LORA_OK) return rc;
     if (layer < 0 || layer >= pool->d.n_layers || proj < 0 || proj >= pool->d.n_proj)
         return LORA_ERR_BAD_SHAPE;
@@ -797,7 +841,7 @@ int lora_expand(const lora_pool *pool, int layer, int proj, float *v,
 {
     int rc = check_pool(pool);
     if (rc != LORA_OK) return rc;
-    rc = check_segments(seg);
+    rc = check_segments(pool, seg);
     if (rc != LORA_OK) return rc;
     if (layer < 0 || layer >= pool->d.n_layers || proj < 0 || proj >= pool->d.n_proj)
         return LORA_ERR_BAD_SHAPE;
@@ -817,7 +861,7 @@ int lora_apply(const lora_pool *pool, int layer, int proj, const void *x, int64_
 {
     int rc = check_pool(pool);
     if (rc != LORA_OK) return rc;
-    rc = check_segments(seg);
+    rc = check_segments(pool, seg);
     if (rc != LORA_OK) return rc;
     if (layer < 0 || layer >= pool->d.n_layers || proj < 0 || proj >= pool->d.n_proj)
         return LORA_ERR_BAD_SHAPE;
@@ -849,7 +893,7 @@ int lora_apply_group(const lora_pool *pool, int layer, int proj0, int n_proj, co
 {
     int rc = check_pool(pool);
     if (rc != LORA_OK) return rc;
-    rc = check_segments(seg);
+    rc = check_segments(pool, seg);
     if (rc != LORA_OK) return rc;
     const lora_pool_desc &d = pool->d;
     if (n_proj < 1 || n_proj > kMaxFused) return LORA_ERR_INVALID_ARG;
@@ -898,7 +942,7 @@ int moe_common_checks(const lora_pool *pool, int layer, int which, const lora_se
 {
     int rc = check_pool(pool);
     if (rc != LORA_OK) return rc;
-    rc = check_segments(seg);
+    rc = check_segments(pool, seg);
     if (rc != LORA_OK) return rc;
     if (which != LORA_MOE_UPGATE && which != LORA_MOE_DOWN) return LORA_ERR_INVALID_ARG;
     const lora_pool_desc &d = pool->d;

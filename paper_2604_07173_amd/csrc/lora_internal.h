@@ -125,6 +125,8 @@ hipError_t launch_pack_B(const PackParams &p, hipStream_t s);
 hipError_t launch_pack_layer(const PackLayerParams &p, hipStream_t s);
 hipError_t launch_unpack_A(const PackParams &p, hipStream_t s);   // src = packed, dst = row-major
 hipError_t launch_unpack_B(const PackParams &p, hipStream_t s);
+hipError_t launch_set_adapter(Unit *table, int n_layers, int n_adapters, int per_adapter, int adapter,
+                              int rank, float scale, hipStream_t s);
 hipError_t launch_segments(const SegParams &p, hipStream_t s);
 hipError_t launch_shrink(const ShrinkParams &p, hipStream_t s);
 int shrink_long_tiles();                                 // tiles per work item of launch_shrink

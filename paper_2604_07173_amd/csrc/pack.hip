@@ -73,6 +73,30 @@ __global__ __launch_bounds__(256) void pack_layer_kernel(PackLayerParams ps)
     else pack_A_body<0>(ps.job[job], gid, blockIdx.y);
 }
 
+// scale and rank of one adapter's table entries, all layers: entry (layer, adapter, e, j) sits
+// at ((layer * n_adapters + adapter) * per_adapter + (e * n_proj + j))
+__global__ __launch_bounds__(256) void set_adapter_kernel(Unit *table, int n_layers, int n_adapters,
+                                                          int per_adapter, int adapter, int rank,
+                                                          float scale)
+{
+    const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (gid >= (int64_t)n_layers * per_adapter) return;
+    const int layer = (int)(gid / per_adapter), k = (int)(gid % per_adapter);
+    Unit *u = table + ((int64_t)layer * n_adapters + adapter) * per_adapter + k;
+    u->scale = scale;
+    u->rank = rank;
+}
+
+hipError_t launch_set_adapter(Unit *table, int n_layers, int n_adapters, int per_adapter, int adapter,
+                              int rank, float scale, hipStream_t s)
+{
+    const int64_t n = (int64_t)n_layers * per_adapter;
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(set_adapter_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, table,
+                       n_layers, n_adapters, per_adapter, adapter, rank, scale);
+    return hipGetLastError();
+}
+
 template <typename K>
 static hipError_t launch_pack(K kernel, const PackParams &p, int64_t groups, hipStream_t s)
 {

@@ -8,7 +8,7 @@ import torch
 import workloads as W
 from gpu_common import check_accumulate, check_delta, oracle_projection
 from oracle import lora_oracle as O
-from paper_2604_07173_amd.harness import DeviceBatch, DevicePool, LayerRunner, bits_from_dev
+from harness import DeviceBatch, DevicePool, LayerRunner, bits_from_dev
 
 pytestmark = pytest.mark.gpu
 
@@ -61,10 +61,67 @@ def test_mixtral_moe_decode(y_mode):
     run_config("mixtral_moe_decode", 1234, y_mode, n_layers=2, layer=1)
 
 
-def test_finegrained_moe_decode():
-    run_config("finegrained_moe_decode", 1234, "normal")
+@pytest.mark.parametrize("y_mode", ["zero", "normal"])
+def test_finegrained_moe_decode(y_mode):
+    run_config("finegrained_moe_decode", 1234, y_mode)
 
 
 def test_prefill_sampled_rows():
     run_config("prefill", 1234, "normal", sample=384)
     run_config("prefill", 1, "zero", sample=128)
+
+
+@pytest.mark.parametrize("y_mode", ["zero", "normal"])
+def test_prefill_one_whole_request(y_mode):
+    """Every row of one 2048-row request of the full prefill batch (64 consecutive 32-row
+    tiles, sixteen four-tile groups of the shrink, all column chunks of both projections),
+    next to the sampled rows of the test above."""
+    name, seed, request = "prefill", 2, 3
+    w = W.WORKLOADS[name]
+    b = W.make_batch(w, seed, y_mode=y_mode)
+    ws = W.make_weights(w, seed)
+    dp, db = DevicePool(ws, b.scale), DeviceBatch(b)
+    LayerRunner(dp, db).step(0)
+    torch.cuda.synchronize()
+    assert db.seg.c.tile_rows == 32
+    per = w.tokens // w.n_requests
+    rows = np.arange(request * per, (request + 1) * per)
+    assert (b.adapter_id[rows] == request).all() and (b.adapter_id == request).sum() == per
+    for j, p in enumerate(w.projs):
+        res = oracle_projection(b, ws, 0, j, rows=rows)
+        got = np.ascontiguousarray(bits_from_dev(db.y[p.name])[rows])
+        if y_mode == "zero":
+            check_delta(W.bf16_bits_to_f32(got).astype(np.float64), res.delta, f"prefill request/{p.name}")
+        else:
+            check_accumulate(got, res, f"prefill request/{p.name}")
+    del dp, db
+    torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("y_mode", ["zero", "normal"])
+@pytest.mark.parametrize("rank", [32, 64])
+def test_mixtral_widths_at_rank_32_and_64(rank, y_mode):
+    """The decode kernels (16-row tiles) at the ranks of the paper's evaluation (Table 3) and
+    the full Mixtral widths 4096 -> 14336 and 14336 -> 4096: the kernel-microbenchmark shape of
+    App. A.2.2 with the adapter count and the batch cut so that the pool and the oracle stay
+    small (16 adapters x 8 experts, 256 tokens x top-2, Zipf 1.2)."""
+    w = W.scaled(W.WORKLOADS["mixtral_r64_microbench"], n_adapters=16, tokens=256, rank=rank)
+    b = W.make_batch(w, 7, y_mode=y_mode, no_adapter_frac=0.03)
+    ws = W.make_weights(w, 7)
+    dp, db = DevicePool(ws, b.scale), DeviceBatch(b)
+    LayerRunner(dp, db).step(0)
+    torch.cuda.synchronize()
+    assert db.seg.c.tile_rows == 16
+    counts = db.seg.counts.cpu().numpy()
+    assert counts[2] > counts[0] > 60          # several segments span more than one tile
+    for j, p in enumerate(w.projs):
+        res = oracle_projection(b, ws, 0, j)
+        got = bits_from_dev(db.y[p.name])
+        if y_mode == "zero":
+            check_delta(W.bf16_bits_to_f32(got).astype(np.float64), res.delta, f"mixtral r{rank}/{p.name}")
+        else:
+            check_accumulate(got, res, f"mixtral r{rank}/{p.name}")
+        none = b.adapter_id < 0
+        assert np.array_equal(got[none], b.y_in[p.name][none])
+    del dp, db
+    torch.cuda.empty_cache()

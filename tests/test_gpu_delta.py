@@ -7,7 +7,7 @@ import torch
 import paper_2604_07173_amd as L
 import workloads as W
 from gpu_common import check_accumulate, check_delta, oracle_projection
-from paper_2604_07173_amd.harness import DeviceBatch, DevicePool, LayerRunner, bits_from_dev, to_dev
+from harness import DeviceBatch, DevicePool, LayerRunner, bits_from_dev, to_dev
 
 pytestmark = pytest.mark.gpu
 
@@ -114,16 +114,20 @@ def test_segments_of_several_16_row_tiles(rank, n, tokens, out_f32):
         check_accumulate(got, res, f"r{rank} n{n} t{tokens}")
 
 
+@pytest.mark.parametrize("y_mode", ["zero", "normal"])
 @pytest.mark.parametrize("rank,h_in", [(8, 200), (8, 64), (16, 200), (32, 104), (64, 72)])
-def test_thousands_of_small_tiles_one_wave_per_tile(rank, h_in):
+def test_thousands_of_small_tiles_one_wave_per_tile(rank, h_in, y_mode):
     """More than 4096 tiles over a short K range: the shrink runs one wave per tile with the
     K range not split (one K part)."""
     w = dense_workload(rank, h_in, 136, n=4400, tokens=4500)
-    b, ws, got, (dp, db, run) = run_dense(w, 21, "normal", drop=0.02)
+    b, ws, got, (dp, db, run) = run_dense(w, 21, y_mode, drop=0.02)
     assert L.lora_v_bytes(dp.pool, 0, 4500) < 2 * 4500 * rank * 4      # a single K part
     assert int(db.seg.counts.cpu()[2]) > 2000
     res = oracle_projection(b, ws, 0, 0)
-    check_accumulate(got, res, f"wave per tile r{rank}")
+    if y_mode == "zero":
+        check_delta(W.bf16_bits_to_f32(got).astype(np.float64), res.delta, f"wave per tile r{rank} k{h_in}")
+    else:
+        check_accumulate(got, res, f"wave per tile r{rank} k{h_in}")
 
 
 @pytest.mark.parametrize("out_f32", [False, True])
@@ -182,17 +186,22 @@ def test_group_of_three_projections_matches_single_calls(rank, tokens, n):
         check_accumulate(bits_from_dev(db.y[p.name]), oracle_projection(b, ws, 0, j), p.name)
 
 
+@pytest.mark.parametrize("y_mode", ["zero", "normal"])
 @pytest.mark.parametrize("rank", [16, 64])
-def test_long_segment_kernels_with_many_short_segments(rank):
+def test_long_segment_kernels_with_many_short_segments(rank, y_mode):
     """P >= 64 * n_keys selects the 32-row-tile kernels; a Zipf draw over 24 adapters then
     leaves many segments of a few rows next to long ones, so most four-tile groups of the
     shrink straddle a segment boundary and the expand reloads B inside its tile groups."""
     w = W.Workload("t", "dense", 24, 1, 1, rank, (W.Proj("p", 328, 264, "x"),), 2048, "zipf", 1.3)
-    b, ws, got, (dp, db, run) = run_dense(w, 51, "normal", drop=0.05)
+    b, ws, got, (dp, db, run) = run_dense(w, 51, y_mode, drop=0.05)
     assert db.seg.c.tile_rows == 32
     lens = np.bincount(b.adapter_id[b.adapter_id >= 0], minlength=24)
     assert lens.max() > 300 and (lens[lens > 0] < 32).sum() >= 4
-    check_accumulate(got, oracle_projection(b, ws, 0, 0), f"long kernels, short segments r{rank}")
+    res = oracle_projection(b, ws, 0, 0)
+    if y_mode == "zero":
+        check_delta(W.bf16_bits_to_f32(got).astype(np.float64), res.delta, f"long kernels, short segments r{rank}")
+    else:
+        check_accumulate(got, res, f"long kernels, short segments r{rank}")
 
 
 @pytest.mark.parametrize("tokens", [1, 40, 5000])

@@ -5,7 +5,7 @@ import pytest
 import torch
 
 import workloads as W
-from paper_2604_07173_amd.harness import DeviceBatch, DevicePool, LayerRunner
+from harness import DeviceBatch, DevicePool, LayerRunner
 
 pytestmark = pytest.mark.gpu
 

@@ -6,7 +6,7 @@ import torch
 
 import paper_2604_07173_amd as L
 import workloads as W
-from paper_2604_07173_amd.harness import DevicePool, bits_from_dev, to_dev
+from harness import DevicePool, bits_from_dev, to_dev
 
 pytestmark = pytest.mark.gpu
 
@@ -114,7 +114,7 @@ def test_layerwise_loading_on_a_second_stream_overlaps_with_compute():
     compute stream waits for a layer's event, then runs that layer.  Every layer's output
     must match the oracle."""
     from gpu_common import check_accumulate, oracle_projection
-    from paper_2604_07173_amd.harness import DeviceBatch, LayerRunner
+    from harness import DeviceBatch, LayerRunner
 
     n_layers = 4
     w = W.Workload("t", "dense", 6, 1, 1, 16, (W.Proj("p", 264, 392, "x"),), 80, "uniform", 0.0)
@@ -176,7 +176,7 @@ def test_async_adapter_load_layer_by_layer_matches_oracle():
     memory on a loading stream, layer after layer; the compute stream waits for a layer of
     all adapters, then runs that layer.  Every layer's output must match the oracle."""
     from gpu_common import check_accumulate, oracle_projection
-    from paper_2604_07173_amd.harness import DeviceBatch
+    from harness import DeviceBatch
 
     n_layers = 5
     w, b, ws, pool, slab = _async_case(n_layers)
@@ -224,7 +224,7 @@ def test_async_load_replaces_an_adapter_in_its_slot():
     """A second load into the same slot (eviction) ordered behind the work that used the
     first: results switch from the first adapter's weights to the second's."""
     from gpu_common import check_accumulate, oracle_projection
-    from paper_2604_07173_amd.harness import DeviceBatch
+    from harness import DeviceBatch
 
     n_layers = 2
     w, b, ws, pool, slab = _async_case(n_layers, seed=85)
@@ -252,6 +252,71 @@ def test_async_load_replaces_an_adapter_in_its_slot():
             L.lora_apply(pool, 1, 0, x, x.shape[1], db.token_of_pair, db.seg, y, y.shape[1], v, stream=stream)
         torch.cuda.synchronize()
         check_accumulate(bits_from_dev(y), oracle_projection(b, src, 1, 0), "slot contents")
+
+
+def test_slot_replacement_with_another_rank_and_scale():
+    """Sec. 4.2: the resident set changes over time.  A slot that held a rank-16 adapter takes a
+    rank-8 adapter with another scale: lora_pool_set_adapter rewrites the slot's table entries
+    and the source stride of later loads, the load zero-pads the lower rank.  Rows of the
+    replaced slot must follow the new adapter and scale, all other rows stay as they were."""
+    from gpu_common import check_accumulate, check_delta, oracle_projection
+    from harness import DeviceBatch
+
+    n_layers, slot, new_scale = 2, 1, 0.75
+    w, b, ws, pool, slab = _async_case(n_layers, seed=87)
+    w8 = W.scaled(w, rank=8)
+    ws8 = W.make_weights(w8, 88, n_layers=n_layers, bank_elems=1 << 21)
+    win = L.lora_pool_adapter_layer_bytes(pool, 0) // 2
+
+    def pinned(src, a, n):
+        rows = [src.bank[int(src.window[a, l]):int(src.window[a, l]) + n].view(np.int16) for l in range(n_layers)]
+        return torch.from_numpy(np.concatenate(rows)).pin_memory()
+
+    staging = torch.empty(win, dtype=torch.int16, device="cuda")
+    stream = torch.cuda.Stream()
+    b0 = W.make_batch(w, 87, y_mode="zero", hetero_scale=True)
+    assert (b0.adapter_id == slot).any() and (b0.adapter_id != slot).any()
+    db = DeviceBatch(b0)
+    v = torch.empty(max(L.lora_v_bytes(pool, 0, db.P), 256) // 4, dtype=torch.float32, device="cuda")
+    hosts = [pinned(ws, a, win) for a in range(w.n_adapters)]
+    with torch.cuda.stream(stream):
+        for a in range(w.n_adapters):
+            L.lora_pool_load_adapter_async(pool, a, hosts[a], staging, load_stream=stream)
+        # the replacement: table first, then the load that reads its source at the new rank
+        L.lora_pool_set_adapter(pool, slot, 8, new_scale, stream=stream)
+        win8 = L.lora_pool_adapter_layer_bytes(pool, slot) // 2
+        assert win8 * 2 == win
+        host8 = pinned(ws8, slot, win8)
+        L.lora_pool_load_adapter_async(pool, slot, host8, staging, load_stream=stream)
+        L.lora_build_segments(pool, db.adapter_id, db.expert_id, db.P, db.seg, stream=stream)
+        y = to_dev(b0.y_in["up"])
+        x = db.inputs["x"]
+        L.lora_apply(pool, 1, 0, x, x.shape[1], db.token_of_pair, db.seg, y, y.shape[1], v, stream=stream)
+    torch.cuda.synchronize()
+    lay = L.lora_pool_unit_layout(pool, slot, 1, 2, 0)
+    assert lay["rank"] == 8 and lay["scale"] == new_scale
+    assert L.lora_pool_unit_layout(pool, 0, 1, 2, 0)["rank"] == 16
+    got = W.bf16_bits_to_f32(bits_from_dev(y)).astype(np.float64)
+    mine = np.flatnonzero(b0.adapter_id == slot)
+    rest = np.flatnonzero(b0.adapter_id != slot)
+    b_new = W.Batch(w, b0.adapter_id, b0.expert_id, b0.token_of_pair, b0.inputs, b0.y_in, b0.scale.copy())
+    b_new.scale[slot] = new_scale
+    check_delta(got[mine], oracle_projection(b_new, ws8, 1, 0, rows=mine).delta, "replaced slot")
+    check_delta(got[rest], oracle_projection(b0, ws, 1, 0, rows=rest).delta, "other slots")
+    # the padding rank entries of the slot read back as zeros
+    p0 = w.projs[0]
+    A_out = torch.full((p0.h_in, 16), -1, dtype=torch.int16, device="cuda")
+    B_out = torch.full((16, p0.h_out), -1, dtype=torch.int16, device="cuda")
+    L.lora_pool_read_unit(pool, slot, 1, 2, 0, A_out, B_out)
+    torch.cuda.synchronize()
+    A, B = ws8.unit_arrays(slot, 1, 2, 0)
+    assert np.array_equal(bits_from_dev(A_out)[:, :8], A) and not bits_from_dev(A_out)[:, 8:].any()
+    assert np.array_equal(bits_from_dev(B_out)[:8], B) and not bits_from_dev(B_out)[8:].any()
+    for args, status in [((slot, 0, 1.0), -3), ((slot, 17, 1.0), -3), ((99, 8, 1.0), -2),
+                         ((slot, 8, float("nan")), -1)]:
+        with pytest.raises(L.LoraError) as e:
+            L.lora_pool_set_adapter(pool, *args)
+        assert e.value.status == status, args
 
 
 def test_async_load_argument_errors():

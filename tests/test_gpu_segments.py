@@ -6,7 +6,7 @@ import torch
 import paper_2604_07173_amd as L
 import workloads as W
 from oracle import lora_oracle as O
-from paper_2604_07173_amd.harness import to_dev
+from harness import to_dev
 
 pytestmark = pytest.mark.gpu
 
