@@ -27,6 +27,14 @@ def pytest_sessionfinish(session, exitstatus):
     out_dir = os.path.join(ROOT, "gpurun_out")
     if not gpu_common.MEASURED or not os.path.isdir(out_dir):
         return
-    rows = [dict(kind=k, what=w, **v) for (k, w), v in sorted(gpu_common.MEASURED.items())]
-    with open(os.path.join(out_dir, "parity_measured.json"), "w") as f:
-        json.dump(rows, f, indent=1)
+    path = os.path.join(out_dir, "parity_measured.json")
+    merged = {}
+    if os.path.exists(path):                 # several pytest processes of one run add to one file
+        try:
+            merged = {(r["kind"], r["what"]): r for r in json.load(open(path))}
+        except (ValueError, KeyError):
+            merged = {}
+    for (k, w), v in gpu_common.MEASURED.items():
+        merged[(k, w)] = dict(kind=k, what=w, **v)
+    with open(path, "w") as f:
+        json.dump([merged[key] for key in sorted(merged)], f, indent=1)
