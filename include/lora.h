@@ -292,6 +292,28 @@ int lora_moe_apply(const lora_pool *pool, int layer, int which, const void *in, 
                    void *y0, void *y1, int64_t ldy, void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * lora_moe_apply for callers that cannot allocate device memory and have no workspace to hand
+ * over: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, checks, kernels and results as lora_moe_apply, but the intermediate lives in
+ * a device array of LORA_STATIC_WS_BYTES that is part of the library's code object (every GPU
+ * the library runs on holds its own copy until the process ends).  The call allocates nothing.
+ *   - LORA_ERR_TOO_LARGE if lora_moe_ws_bytes(pool, seg->P) exceeds LORA_STATIC_WS_BYTES;
+ *     nothing is enqueued then.
+ *   - All calls on one GPU share the one array: two calls whose device work can overlap (two
+ *     streams, two threads) race; keep them on one stream or order them with events.  The array
+ *     keeps the previous call's contents; nothing in it needs clearing, because the shrink
+ *     writes every value the expand reads.
+ *   - The array's device address is looked up once per device, in lora_register_pool (or in the
+ *     first call here on a device that registered no pool); that lookup is a runtime query, so
+ *     let it happen before a graph capture starts.
+ */
+enum { LORA_STATIC_WS_BYTES = 16 << 20 };
+
+int lora_moe_apply_static(const lora_pool *pool, int layer, int which, const void *in, int64_t ld_in,
+                          const int32_t *token_of_pair, const lora_segments *seg,
+                          void *y0, void *y1, int64_t ldy, void *stream);
+
+/*
  * The two phases of lora_moe_apply as separate calls (App. A.2.2 reports shrink and expand
  * separately): lora_moe_shrink leaves the intermediate in ws, lora_moe_expand consumes it.
  * lora_moe_apply(...) is exactly lora_moe_shrink(...) followed by lora_moe_expand(...) with

@@ -14,6 +14,7 @@ LORA_DTYPE_BF16, LORA_DTYPE_F32 = 0, 1
 LORA_MOE_UPGATE, LORA_MOE_DOWN = 0, 1
 LORA_MAX_PROJ = 8
 LORA_MAX_ROWS = 1 << 14
+LORA_STATIC_WS_BYTES = 16 << 20
 
 EXPORTED_SYMBOLS = [
     "lora_strerror", "lora_last_hip_error", "lora_pool_bytes", "lora_register_pool",
@@ -21,7 +22,7 @@ EXPORTED_SYMBOLS = [
     "lora_pool_load_adapter_async", "lora_pool_set_adapter", "lora_pool_wait_layer", "lora_pool_layer_ready", "lora_pool_read_unit",
     "lora_pool_unit_layout", "lora_pool_device_table", "lora_pool_destroy",
     "lora_segments_ws_bytes", "lora_build_segments", "lora_v_bytes", "lora_shrink",
-    "lora_expand", "lora_apply", "lora_group_ws_bytes", "lora_apply_group", "lora_moe_ws_bytes", "lora_moe_apply", "lora_moe_shrink", "lora_moe_expand",
+    "lora_expand", "lora_apply", "lora_group_ws_bytes", "lora_apply_group", "lora_moe_ws_bytes", "lora_moe_apply", "lora_moe_apply_static", "lora_moe_shrink", "lora_moe_expand",
 ]
 
 
@@ -127,6 +128,8 @@ def load_library():
     lib.lora_moe_apply.restype = i32
     lib.lora_moe_apply.argtypes = [vp, i32, i32, vp, i64, vp, C.POINTER(_Segments), vp, vp, i64,
                                    vp, sz, vp]
+    lib.lora_moe_apply_static.restype = i32
+    lib.lora_moe_apply_static.argtypes = [vp, i32, i32, vp, i64, vp, C.POINTER(_Segments), vp, vp, i64, vp]
     lib.lora_moe_shrink.restype = i32
     lib.lora_moe_shrink.argtypes = [vp, i32, i32, vp, i64, vp, C.POINTER(_Segments), vp, sz, vp]
     lib.lora_moe_expand.restype = i32
@@ -391,6 +394,14 @@ def lora_moe_apply(pool, layer, which, inp, ld_in, token_of_pair, seg: Segments,
                                          _addr(token_of_pair), C.byref(seg.c), _addr(y0),
                                          _addr(y1), ldy, _addr(ws), ws_bytes, _stream(stream)),
            "lora_moe_apply")
+
+
+def lora_moe_apply_static(pool, layer, which, inp, ld_in, token_of_pair, seg: Segments, y0, y1, ldy,
+                          stream=None):
+    _check(load_library().lora_moe_apply_static(_h(pool), layer, which, _addr(inp), ld_in,
+                                                _addr(token_of_pair), C.byref(seg.c), _addr(y0),
+                                                _addr(y1), ldy, _stream(stream)),
+           "lora_moe_apply_static")
 
 
 def lora_moe_shrink(pool, layer, which, inp, ld_in, token_of_pair, seg: Segments, ws,

@@ -6,6 +6,7 @@
 
 #include <algorithm>
 #include <cmath>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -71,6 +72,39 @@ int cu_count()
             n = 256;
     }
     return n;
+}
+
+// Workspace of lora_moe_apply_static: one array per GPU, part of the loaded code object, so
+// no call ever allocates it.  In host code the name below is only a handle for
+// hipGetSymbolAddress; the address kernels and copies use is the one that call returns, looked
+// up once per device with that device current and kept in g_scratch_ptr.
+constexpr size_t kStaticScratchBytes = LORA_STATIC_WS_BYTES;
+
+}  // namespace
+
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices];
+
+// address of `scratch` on the current device (resolved on the first call per device)
+int static_scratch(void **out)
+{
+    int dev = -1;
+    LORA_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return LORA_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        LORA_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) return LORA_ERR_HIP;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return LORA_OK;
 }
 
 }  // namespace
@@ -509,6 +543,16 @@ int lora_register_pool(const lora_pool_desc *d, void *slab, size_t slab_bytes,
                     u.pad[0] = u.pad[1] = 0;
                 }
 
+    {
+        // set-up of this device: the address of the static workspace of lora_moe_apply_static
+        void *unused = nullptr;
+        rc = static_scratch(&unused);
+        if (rc != LORA_OK) {
+            p->magic = 0;
+            delete p;
+            return rc;
+        }
+    }
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipError_t e = hipMemcpyAsync(p->slab, p->table.data(), p->table.size() * sizeof(Unit),
                                   hipMemcpyHostToDevice, st);
@@ -1036,6 +1080,22 @@ int lora_moe_expand(const lora_pool *pool, int layer, int which, const lora_segm
     if (rc != LORA_OK) return rc;
     return moe_expand_launch(pool, layer, which, seg, y0, y1, ldy, ws,
                              static_cast<hipStream_t>(stream));
+}
+
+int lora_moe_apply_static(const lora_pool *pool, int layer, int which, const void *in, int64_t ld_in,
+                          const int32_t *token_of_pair, const lora_segments *seg, void *y0, void *y1,
+                          int64_t ldy, void *stream)
+{
+    int rc = check_pool(pool);
+    if (rc != LORA_OK) return rc;
+    if (!seg) return LORA_ERR_INVALID_ARG;
+    if (seg->P > 0 && pool->d.n_proj >= 3 && lora_moe_ws_bytes(pool, seg->P) > kStaticScratchBytes)
+        return LORA_ERR_TOO_LARGE;
+    void *ws = nullptr;
+    rc = static_scratch(&ws);            // the device address, never the array's name
+    if (rc != LORA_OK) return rc;
+    return lora_moe_apply(pool, layer, which, in, ld_in, token_of_pair, seg, y0, y1, ldy, ws,
+                          kStaticScratchBytes, stream);
 }
 
 int lora_moe_apply(const lora_pool *pool, int layer, int which, const void *in, int64_t ld_in,
