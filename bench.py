@@ -133,6 +133,7 @@ def measure(name, args, steps, warmup, with_cpu_baseline):
     t1 = time.perf_counter()
     stream_ms_per_step = (t1 - t0) * 1e3 / steps
     ms_per_step = stream_ms_per_step
+    replay_ms = []
     if args.launch == "graph":
         # the same K steps recorded once into a HIP graph and replayed: no allocation, no
         # synchronisation and no memset inside, so the library's launches capture as they are
@@ -145,11 +146,19 @@ def measure(name, args, steps, warmup, with_cpu_baseline):
         torch.cuda.synchronize()
         graph.replay()                      # untimed: first replay uploads the graph
         torch.cuda.synchronize()
+        # the timed region: EXACTLY `steps` steps (one replay); further replays of the same
+        # graph only tell how far single measurements scatter
         t0 = time.perf_counter()
         graph.replay()
         torch.cuda.synchronize()
         t1 = time.perf_counter()
         ms_per_step = (t1 - t0) * 1e3 / steps
+        for _ in range(9):
+            t0 = time.perf_counter()
+            graph.replay()
+            torch.cuda.synchronize()
+            replay_ms.append((time.perf_counter() - t0) * 1e3 / steps)
+        replay_ms.append(ms_per_step)
         del graph
 
     # ---- the same steps without the segment build (App. A.2.2 times shrink and expand only) --
@@ -220,14 +229,16 @@ def measure(name, args, steps, warmup, with_cpu_baseline):
                                   gbs=float(ph.bytes / (us * 1e-6) / 1e9))
     dom = max(phases[1:], key=lambda ph: per_phase[ph.name]["us"])
     d = per_phase[dom.name]
+    traffic, traffic_note = read_traffic(name, dom.name)
     roofline = dict(bound="hbm", kernel=dom.name, achieved=round(d["gbs"], 1), peak=HBM_PEAK_GBS,
                     unit="GB/s", frac=round(d["gbs"] / HBM_PEAK_GBS, 4),
-                    traffic=read_traffic(name, dom.name), us_per_launch=round(d["us"], 2),
+                    traffic=traffic, traffic_source=traffic_note, us_per_launch=round(d["us"], 2),
                     algorithmic_bytes=int(dom.bytes))
 
     total_bytes = acct["total"]
     res = dict(
         workload=name, ms_per_step=ms_per_step, stream_ms_per_step=stream_ms_per_step,
+        replay_ms=sorted(replay_ms),
         nobuild_ms_per_step=nobuild_ms_per_step,
         step_us_p10=float(np.percentile(per_step_us, 10)), step_us_p50=float(np.percentile(per_step_us, 50)),
         step_us_p90=float(np.percentile(per_step_us, 90)),
@@ -268,20 +279,44 @@ def copy_ceiling_gbs():
     return 2 * (1 << 30) / (ms * 1e-3) / 1e9
 
 
+def kernel_sources_digest():
+    """Digest of the kernel sources the library is built from: a counter summary under profiles/
+    names the digest it was taken with, so a summary of other kernels is recognised as stale."""
+    import hashlib
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2604_07173_amd", "csrc")
+    for fn in sorted(os.listdir(csrc)):
+        if fn.endswith((".hip", ".h")):
+            h.update(fn.encode())
+            h.update(open(os.path.join(csrc, fn), "rb").read())
+    return h.hexdigest()[:16]
+
+
 def read_traffic(workload, kernel):
-    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), if a summary
-    for this workload and kernel is on file under profiles/."""
+    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE) in separate
+    runs of this program, taken from the summary on file under profiles/.  The counters cannot
+    be read from inside a timed run, so the figure is a measurement of an earlier run of the
+    same kernels: it is reported only if the summary names the digest of the present kernel
+    sources; otherwise traffic is null and the note says why."""
     path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
     if not os.path.exists(path):
-        return None
+        return None, "no counter summary on file for this workload"
+    value, digest = None, None
     for line in open(path):
         parts = line.split()
         if len(parts) >= 2 and parts[0] == f"{kernel}_traffic_bytes_per_launch:":
             try:
-                return int(float(parts[1]))
+                value = int(float(parts[1]))
             except ValueError:
-                return None
-    return None
+                value = None
+        if len(parts) >= 2 and parts[0] == "kernel_sources_digest:":
+            digest = parts[1]
+    rel = os.path.relpath(path, ROOT)
+    if value is None:
+        return None, f"{rel} has no figure for {kernel}"
+    if digest != kernel_sources_digest():
+        return None, f"{rel} was taken with other kernel sources (digest {digest}); not reported"
+    return value, f"{rel} (rocprofv3 --pmc run of the same kernel sources, digest {digest})"
 
 
 def cpu_baseline(w, b, ws):
@@ -307,10 +342,13 @@ def cpu_baseline(w, b, ws):
                     src_row=None if p.input == "mid" else b.token_of_pair, y_in=b.y_in[p.name],
                     want_v=False)
 
+    t0 = time.perf_counter()
     layer_call()                      # first call also builds/loads the oracle
-    times = []
+    first = time.perf_counter() - t0
+    times = [first] if first > 5.0 else []     # a call of many seconds (prefill) is timed once
     t_all = time.perf_counter()
-    while len(times) < 3 or (time.perf_counter() - t_all < 10.0 and len(times) < 20):
+    while not times or (first <= 5.0 and (len(times) < 3 or
+                                          (time.perf_counter() - t_all < 10.0 and len(times) < 20))):
         t0 = time.perf_counter()
         layer_call()
         times.append(time.perf_counter() - t0)
@@ -395,6 +433,14 @@ def measure_adapter_load(args):
                                     "steps_enqueued": n}}
 
 
+def spread(ms):
+    """[min, median, max] of the per-step times of the graph replays (None without a graph)."""
+    if not ms:
+        return None
+    ms = sorted(ms)
+    return [round(ms[0], 5), round(ms[len(ms) // 2], 5), round(ms[-1], 5)]
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -429,6 +475,7 @@ def main():
                    "launch": "one HIP graph of all timed steps" if args.launch == "graph"
                    else "stream launches",
                    "seed": args.seed, "segments": main_res["segments"], "rows": main_res["pairs"]},
+        "graph_replays_ms_per_step_min_median_max": spread(main_res["replay_ms"]),
         "stream_launch_ms_per_step": round(main_res["stream_ms_per_step"], 5),
         "ms_per_step_without_segment_build": round(main_res["nobuild_ms_per_step"], 5),
         "step_us_p10_p50_p90": [round(main_res["step_us_p10"], 2), round(main_res["step_us_p50"], 2),
@@ -456,16 +503,21 @@ def main():
         for name in ("dense_small", "llama8b_decode", "prefill", "finegrained_moe_decode"):
             if name == args.workload:
                 continue
-            r = measure(name, args, max(20, args.steps // 4), max(5, args.warmup // 2), False)
+            r = measure(name, args, max(20, args.steps // 4), max(5, args.warmup // 2),
+                        not args.no_cpu_baseline)
             extra[name] = {"ms_per_step": round(r["ms_per_step"], 5),
                            "tokens_per_s": round(r["tokens_per_s"], 1),
                            "hbm_gbs": round(r["step_gbs"], 1),
                            "hbm_frac_of_peak": round(r["step_frac_of_peak"], 4),
                            "algorithmic_bytes_per_step": r["algorithmic_bytes"],
+                           "graph_replays_ms_per_step_min_median_max": spread(r["replay_ms"]),
                            "two_calls_in_flight_ms_per_step":
                                None if args.no_two_calls else round(r["two_calls"]["ms_per_step"], 5),
                            "phases": {k: {"us": round(v["us"], 2), "GB/s": round(v["gbs"], 1)}
-                                      for k, v in r["phases"].items()}}
+                                      for k, v in r["phases"].items()},
+                           "roofline": r["roofline"]}
+            if "cpu_baseline" in r:
+                extra[name]["cpu_baseline"] = r["cpu_baseline"]
         extra["adapter_load_mixtral"] = measure_adapter_load(args)
         out["extra"] = extra
     print(json.dumps(out))

@@ -15,4 +15,5 @@ from .binding import (  # noqa: F401
     lora_moe_ws_bytes, lora_moe_apply, lora_moe_apply_static, lora_moe_shrink, lora_moe_expand, lora_strerror,
     LORA_DTYPE_BF16, LORA_DTYPE_F32, LORA_MOE_UPGATE, LORA_MOE_DOWN, LORA_MAX_ROWS, LORA_STATIC_WS_BYTES,
     EXPORTED_SYMBOLS,
+    ProvisionError, lora_provision_iar, lora_provision_min_cache, lora_provision_memory_bytes,
 )

@@ -22,6 +22,7 @@ EXPORTED_SYMBOLS = [
     "lora_pool_load_adapter_async", "lora_pool_set_adapter", "lora_pool_wait_layer", "lora_pool_layer_ready", "lora_pool_read_unit",
     "lora_pool_unit_layout", "lora_pool_device_table", "lora_pool_destroy",
     "lora_segments_ws_bytes", "lora_build_segments", "lora_v_bytes", "lora_shrink",
+    "lora_provision_iar", "lora_provision_min_cache", "lora_provision_memory_bytes",
     "lora_expand", "lora_apply", "lora_group_ws_bytes", "lora_apply_group", "lora_moe_ws_bytes", "lora_moe_apply", "lora_moe_apply_static", "lora_moe_shrink", "lora_moe_expand",
 ]
 
@@ -134,6 +135,13 @@ def load_library():
     lib.lora_moe_shrink.argtypes = [vp, i32, i32, vp, i64, vp, C.POINTER(_Segments), vp, sz, vp]
     lib.lora_moe_expand.restype = i32
     lib.lora_moe_expand.argtypes = [vp, i32, i32, C.POINTER(_Segments), vp, vp, i64, vp, sz, vp]
+    dp = C.POINTER(C.c_double)
+    lib.lora_provision_iar.restype = i32
+    lib.lora_provision_iar.argtypes = [dp, i32, C.c_double, i32, dp, dp, dp]
+    lib.lora_provision_min_cache.restype = i32
+    lib.lora_provision_min_cache.argtypes = [dp, i32, C.c_double, C.c_double, C.POINTER(C.c_int), dp]
+    lib.lora_provision_memory_bytes.restype = C.c_int64
+    lib.lora_provision_memory_bytes.argtypes = [i32, C.c_int64]
     _lib = lib
     return lib
 
@@ -420,3 +428,43 @@ def lora_moe_expand(pool, layer, which, seg: Segments, y0, y1, ldy, ws, ws_bytes
     _check(load_library().lora_moe_expand(_h(pool), layer, which, C.byref(seg.c), _addr(y0),
                                           _addr(y1), ldy, _addr(ws), ws_bytes, _stream(stream)),
            "lora_moe_expand")
+
+
+# ---- cache provisioning (include/lora_provision.h): host arrays in, numbers out ----------------
+
+
+class ProvisionError(ValueError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: status {status}")
+
+
+def _doubles(values):
+    arr = (C.c_double * len(values))(*[float(v) for v in values])
+    return arr
+
+
+def lora_provision_iar(p, LB: float, M: int):
+    """IAR(M), tau* and the residency probabilities q_i (a list) for invocation probabilities p."""
+    n = len(p)
+    arr, q = _doubles(p), (C.c_double * n)()
+    iar, tau = C.c_double(), C.c_double()
+    st = load_library().lora_provision_iar(arr, n, float(LB), int(M), C.byref(iar), C.byref(tau), q)
+    if st != 0:
+        raise ProvisionError(st, "lora_provision_iar")
+    return iar.value, tau.value, list(q)
+
+
+def lora_provision_min_cache(p, LB: float, alpha: float):
+    """(M*, IAR(M*)): the smallest cache capacity whose IAR reaches alpha."""
+    arr = _doubles(p)
+    m, iar = C.c_int(), C.c_double()
+    st = load_library().lora_provision_min_cache(arr, len(p), float(LB), float(alpha), C.byref(m),
+                                                 C.byref(iar))
+    if st != 0:
+        raise ProvisionError(st, "lora_provision_min_cache")
+    return m.value, iar.value
+
+
+def lora_provision_memory_bytes(M: int, adapter_bytes: int) -> int:
+    return int(load_library().lora_provision_memory_bytes(int(M), int(adapter_bytes)))

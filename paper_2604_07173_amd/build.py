@@ -10,8 +10,9 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "liblora.so")
 SOURCES = ["api.hip", "pack.hip", "segments.hip", "shrink.hip", "expand.hip",
-           "shrink_decode.hip", "expand_decode.hip"]
-HEADERS = ["lora_internal.h", "lora_layout.h", "lora_device.h", "expand_common.h", os.path.join("..", "..", "include", "lora.h")]
+           "shrink_decode.hip", "expand_decode.hip", "provision.cpp"]
+HEADERS = ["lora_internal.h", "lora_layout.h", "lora_device.h", "expand_common.h", os.path.join("..", "..", "include", "lora.h"),
+           os.path.join("..", "..", "include", "lora_provision.h")]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -19,6 +20,9 @@ HIPCC_FLAGS = [
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-function",
 ]
+
+
+HOST_FLAGS = ["-O2", "-std=c++17", "-fPIC", "-Wall"]      # host-only translation units
 
 
 def hipcc() -> str:
@@ -44,9 +48,10 @@ def build(verbose: bool = False, jobs: int = 7) -> str:
     procs = []
     objs = []
     for src in SOURCES:
-        obj = os.path.join(objdir, src.replace(".hip", ".o"))
+        obj = os.path.join(objdir, os.path.splitext(src)[0] + ".o")
         objs.append(obj)
-        cmd = [cc, *HIPCC_FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+        flags = HIPCC_FLAGS if src.endswith(".hip") else HOST_FLAGS
+        cmd = [cc, *flags, "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT)))
