@@ -140,6 +140,46 @@ int lora_oracle_delta(int P, int h_in, int h_out, int r,
 }
 
 /*
+ * Weighted combine of the per-pair updates of the down projection into token rows.
+ *
+ * Sec. 4.1: a request activates its top-k experts at a layer, so a batch of T tokens is
+ * T*k (token, expert) pairs; Sec. 3 / Fig. 7b: the LoRA results come back and are added
+ * to the base output.  In a MoE layer the base output of a token is the routing-weighted
+ * sum of its experts' outputs, and the update belongs to an expert's weight, so the
+ * token's base output gains  sum_j w[t*k+j] * delta[t*k+j]  (the paper does not spell
+ * the routing weights out; this is the reading taken).  Pair p = t*k + j.
+ *
+ *   delta   [T*k][h_out]  per-pair updates as lora_oracle_delta returns them (zero rows
+ *                         for pairs without adapter)
+ *   w       [T*k]         routing weights
+ *   y_in    bf16 bits [T][ldy] token rows of the base output, or NULL (= all zero)
+ *   y_out   [T][h_out]    y_in + sum over j = 0 .. k-1 (ascending) of w * delta, unrounded
+ *   y_bf16  [T][h_out]    y_out rounded once; a token none of whose pairs has an adapter
+ *                         keeps its input bits
+ */
+void lora_oracle_combine(int T, int k, int h_out, const double *delta, const int32_t *adapter_id,
+                         const float *w, const uint16_t *y_in, int64_t ldy,
+                         double *y_out, uint16_t *y_bf16)
+{
+#pragma omp parallel for schedule(static)
+    for (int t = 0; t < T; ++t) {
+        int any = 0;
+        for (int j = 0; j < k; ++j) any |= adapter_id[(size_t)t * k + j] != -1;
+        for (int d = 0; d < h_out; ++d) {
+            uint16_t yb = y_in ? y_in[(size_t)t * ldy + d] : 0;
+            double acc = bf16_to_f64(yb);
+            for (int j = 0; j < k; ++j) {
+                size_t p = (size_t)t * k + j;
+                if (adapter_id[p] != -1) acc += (double)w[p] * delta[p * h_out + d];
+            }
+            size_t o = (size_t)t * h_out + d;
+            if (y_out) y_out[o] = acc;
+            if (y_bf16) y_bf16[o] = any ? f64_to_bf16_rne(acc) : yb;
+        }
+    }
+}
+
+/*
  * Canonical segments (App. A.2.2: rows that share an adapter are aggregated into one
  * GEMM; with per-expert matrices, rows that share (adapter, expert)).  Many groupings
  * give the same sums; the contract fixes one:

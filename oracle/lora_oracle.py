@@ -38,6 +38,9 @@ def _declare(lib):
             C.c_void_p, C.c_void_p, C.c_void_p,
             C.c_void_p, C.c_int64,
             C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        lib.lora_oracle_combine.restype = None
+        lib.lora_oracle_combine.argtypes = [C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
+                                            C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
         lib.lora_oracle_segments.restype = C.c_int
         lib.lora_oracle_segments.argtypes = [C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_int,
                                              C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
@@ -138,6 +141,37 @@ def delta(x: np.ndarray, adapter_id: np.ndarray, A_units: Sequence[Optional[np.n
         n_adapters, n_experts, _ptr(Ap), _ptr(Bp), _ptr(scale), _ptr(y_in), ldy,
         _ptr(res.v), _ptr(res.delta), _ptr(res.y_out), _ptr(res.y_bf16))
     del keep
+    return res
+
+
+class CombineResult:
+    __slots__ = ("y_out", "y_bf16", "combined")
+
+
+def combine(delta: np.ndarray, adapter_id: np.ndarray, route_w: np.ndarray, top_k: int,
+            y_in: Optional[np.ndarray] = None) -> CombineResult:
+    """Token rows after the routing-weighted combine of the per-pair updates `delta`
+    ([T*k][h_out] float64, as delta() returns them).  adapter_id: per pair, -1 = no adapter
+    (out-of-range ids must already have been mapped to -1).  y_in: bf16 bits [T][h_out]."""
+    lib = _load()
+    delta = np.ascontiguousarray(delta, dtype=np.float64)
+    P, h_out = delta.shape
+    assert P % top_k == 0
+    T = P // top_k
+    adapter_id = np.ascontiguousarray(adapter_id, dtype=np.int32)
+    route_w = np.ascontiguousarray(route_w, dtype=np.float32)
+    assert adapter_id.shape == (P,) and route_w.shape == (P,)
+    ldy = 0
+    if y_in is not None:
+        assert y_in.dtype == np.uint16 and y_in.shape == (T, h_out) and y_in.strides[1] == 2
+        ldy = y_in.strides[0] // 2
+    res = CombineResult()
+    res.y_out = np.empty((T, h_out), dtype=np.float64)
+    res.y_bf16 = np.empty((T, h_out), dtype=np.uint16)
+    lib.lora_oracle_combine(T, top_k, h_out, _ptr(delta), _ptr(adapter_id), _ptr(route_w),
+                            _ptr(y_in), ldy, _ptr(res.y_out), _ptr(res.y_bf16))
+    base = 0.0 if y_in is None else (y_in.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+    res.combined = res.y_out - base
     return res
 
 

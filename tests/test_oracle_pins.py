@@ -336,3 +336,101 @@ def test_workload_structure_matches_paper_counts():
     assert ss.S < s.S < 4 * ss.S
     # every token's k experts are distinct
     assert all(len(set(r)) == w.top_k for r in b.expert_id.reshape(-1, w.top_k))
+
+
+# ------------------------------------------------------------------ weighted top-k combine
+
+
+def combine_case(seed, T=7, k=3, h=24, r=4, d=16, n=3, E=4, drop=0.2):
+    """Per-pair updates of a small MoE down projection plus routing weights and token rows."""
+    rng = np.random.default_rng(seed)
+    P = T * k
+    x = bits(rng.standard_normal((P, h)))
+    A = [bits(rng.standard_normal((h, r)) * 0.5) for _ in range(n * E)]
+    B = [bits(rng.standard_normal((r, d)) * 0.5) for _ in range(n * E)]
+    tok_a = rng.integers(0, n, size=T).astype(np.int32)
+    tok_a[rng.random(T) < drop] = -1
+    aid = np.repeat(tok_a, k).astype(np.int32)
+    eid = np.stack([rng.permutation(E)[:k] for _ in range(T)]).reshape(P).astype(np.int32)
+    scale = (0.5 + rng.random(n)).astype(np.float32)
+    w = rng.random(P).astype(np.float32)
+    y = bits(rng.standard_normal((T, d)))
+    res = O.delta(x, aid, A, B, scale, n_adapters=n, n_experts=E, expert_id=eid)
+    return dict(x=x, A=A, B=B, aid=aid, eid=eid, scale=scale, w=w, y=y, delta=res.delta, T=T, k=k,
+                n=n, E=E)
+
+
+def test_combine_hand_example(golden_dir):
+    g = _read_golden(os.path.join(golden_dir, "combine_hand_example.txt"))
+    k, d = int(g["k"][0][0]), int(g["h_out"][0][0])
+    delta = np.array(g["delta"][0]).reshape(-1, d)
+    res = O.combine(delta, np.array(g["adapter"][0], np.int32), np.array(g["w"][0], np.float32), k,
+                    y_in=bits(np.array(g["y_in"][0]).reshape(-1, d)))
+    assert res.y_out.reshape(-1).tolist() == g["y_out"][0]
+    assert f64(res.y_bf16).reshape(-1).tolist() == g["y_out"][0]      # all bf16 values
+
+
+def test_combine_against_a_library_contraction():
+    """sum_j w_j delta_j per token is an einsum over the pair axis."""
+    for seed in range(4):
+        c = combine_case(seed)
+        res = O.combine(c["delta"], c["aid"], c["w"], c["k"], y_in=c["y"])
+        d3 = c["delta"].reshape(c["T"], c["k"], -1)
+        w2 = c["w"].astype(np.float64).reshape(c["T"], c["k"])
+        want = f64(c["y"]) + np.einsum("tj,tjd->td", w2, d3)
+        np.testing.assert_allclose(res.y_out, want, rtol=1e-13, atol=1e-13)
+        np.testing.assert_allclose(res.combined, want - f64(c["y"]), rtol=0, atol=1e-12)
+
+
+def test_combine_with_one_expert_and_unit_weight_is_the_plain_update():
+    """k = 1 and w = 1: the token row receives exactly what the per-row update gives."""
+    x, A, B, aid, eid, scale, y = rand_case(40, E=3)
+    aid[2] = -1
+    plain = O.delta(x, aid, A, B, scale, n_adapters=3, n_experts=3, expert_id=eid, y_in=y)
+    res = O.combine(plain.delta, aid, np.ones(len(aid), np.float32), 1, y_in=y)
+    assert np.array_equal(res.y_out, plain.y_out)
+    assert np.array_equal(res.y_bf16, plain.y_bf16)
+
+
+def test_combine_merged_weight_form():
+    """sum_j w_j s x_j A_j B_j with the products A_j B_j formed first (fp64 re-association)."""
+    c = combine_case(5, T=5, k=2)
+    res = O.combine(c["delta"], c["aid"], c["w"], c["k"])
+    for t in range(c["T"]):
+        want = np.zeros(c["delta"].shape[1])
+        for j in range(c["k"]):
+            p = t * c["k"] + j
+            if c["aid"][p] < 0:
+                continue
+            u = c["aid"][p] * c["E"] + c["eid"][p]
+            W_merged = f64(c["A"][u]) @ f64(c["B"][u])
+            want += float(c["w"][p]) * float(c["scale"][c["aid"][p]]) * (f64(c["x"][p]) @ W_merged)
+        np.testing.assert_allclose(res.y_out[t], want, rtol=1e-12, atol=1e-12)
+
+
+def test_combine_leaves_tokens_without_adapter_untouched_and_is_linear_in_w():
+    c = combine_case(6, drop=0.4)
+    res = O.combine(c["delta"], c["aid"], c["w"], c["k"], y_in=c["y"])
+    tok_none = (c["aid"].reshape(c["T"], c["k"]) < 0).all(axis=1)
+    assert tok_none.any() and not tok_none.all()
+    assert np.array_equal(res.y_bf16[tok_none], c["y"][tok_none])
+    assert np.array_equal(res.y_out[tok_none], f64(c["y"])[tok_none])
+    # zero weights: nothing is added; doubling the weights doubles what is added
+    zero = O.combine(c["delta"], c["aid"], np.zeros_like(c["w"]), c["k"], y_in=c["y"])
+    assert np.array_equal(zero.y_bf16, c["y"])
+    twice = O.combine(c["delta"], c["aid"], 2 * c["w"], c["k"], y_in=c["y"])
+    np.testing.assert_allclose(twice.combined, 2 * res.combined, rtol=1e-14, atol=0)
+    # a pair's garbage update is ignored when the pair has no adapter
+    d2 = c["delta"].copy()
+    d2[c["aid"] < 0] = 1e30
+    assert np.array_equal(O.combine(d2, c["aid"], c["w"], c["k"], y_in=c["y"]).y_out, res.y_out)
+
+
+def test_combine_is_invariant_under_reordering_a_tokens_experts():
+    """The sum over a token's experts does not depend on their order beyond fp64 rounding."""
+    c = combine_case(7, T=6, k=4, E=6)
+    res = O.combine(c["delta"], c["aid"], c["w"], c["k"])
+    rng = np.random.default_rng(7)
+    order = np.concatenate([t * c["k"] + rng.permutation(c["k"]) for t in range(c["T"])])
+    res2 = O.combine(c["delta"][order], c["aid"][order], c["w"][order], c["k"])
+    np.testing.assert_allclose(res2.y_out, res.y_out, rtol=1e-13, atol=1e-13)
