@@ -38,6 +38,10 @@ def parse_args():
                     help="skip the two-calls-in-flight measurement (kernel traces then hold one stream only)")
     ap.add_argument("--all", action="store_true",
                     help="also measure the other workloads and the layer-wise adapter load (extra field)")
+    ap.add_argument("--down-combine", action="store_true",
+                    help="MoE workloads: replace the down application (update added to every pair's "
+                         "row) by lora_moe_down_combine (routing-weighted sum into token rows); "
+                         "a variant for comparison, not the headline")
     ap.add_argument("--launch", choices=["graph", "stream"], default="graph",
                     help="how the timed steps are launched: one HIP graph holding all K steps "
                          "(as a serving engine captures a decode iteration), or plain stream launches")
@@ -56,7 +60,7 @@ class Phase:
         self.name, self.fn, self.bytes = name, fn, bytes_
 
 
-def make_phases(L, W, dp, db, run, acct):
+def make_phases(L, W, dp, db, run, acct, down_combine=False):
     """The launches of one step, each with the algorithmic bytes it must move."""
     w = dp.workload
     pool, seg = dp.pool, db.seg
@@ -75,6 +79,24 @@ def make_phases(L, W, dp, db, run, acct):
             lambda layer: L.lora_moe_expand(pool, layer, L.LORA_MOE_UPGATE, seg, db.y["gate"],
                                             db.y["up"], db.y["gate"].shape[1], run.ws),
             2 * (S * r * g.h_out * 2 + P_act * g.h_out * 4)))
+        if down_combine:
+            import numpy as np
+            import torch
+            from harness import to_dev
+            k, T = w.top_k, w.tokens
+            rng = np.random.default_rng(7)
+            route_w = to_dev(rng.dirichlet(np.ones(k), size=T).astype(np.float32).reshape(-1))
+            y_tok = to_dev(W.f32_to_bf16_bits(rng.standard_normal((T, d.h_out), dtype=np.float32)))
+            cws = torch.empty(L.lora_moe_combine_ws_bytes(pool, db.P), dtype=torch.uint8, device="cuda")
+            # shrink as before; every touched B once; the pair rows written and read once (bf16);
+            # token rows read and written once
+            phases.append(Phase(
+                "down_combine",
+                lambda layer: L.lora_moe_down_combine(pool, layer, mid, mid.shape[1], db.adapter_id,
+                                                      db.expert_id, seg, route_w, k, y_tok, d.h_out, cws),
+                S * r * d.h_in * 2 + P_act * d.h_in * 2 + S * r * d.h_out * 2 + P_act * d.h_out * 4
+                + T_act * d.h_out * 4))
+            return phases
         phases.append(Phase(
             "down_shrink",
             lambda layer: L.lora_moe_shrink(pool, layer, L.LORA_MOE_DOWN, mid, mid.shape[1], None,
@@ -115,7 +137,7 @@ def measure(name, args, steps, warmup, with_cpu_baseline):
     db = DeviceBatch(b)
     run = LayerRunner(dp, db)
     acct = W.algorithmic_bytes(w, b.adapter_id, b.expert_id)
-    phases = make_phases(L, W, dp, db, run, acct)
+    phases = make_phases(L, W, dp, db, run, acct, getattr(args, "down_combine", False) and w.kind == "moe")
 
     def step(it):
         layer = it % n_layers
@@ -474,7 +496,8 @@ def main():
                    "weights": "hot (one layer)" if args.hot else "cold (layer rotation)",
                    "launch": "one HIP graph of all timed steps" if args.launch == "graph"
                    else "stream launches",
-                   "seed": args.seed, "segments": main_res["segments"], "rows": main_res["pairs"]},
+                   "seed": args.seed, "segments": main_res["segments"], "rows": main_res["pairs"],
+                   **({"down": "lora_moe_down_combine (token rows)"} if args.down_combine else {})},
         "graph_replays_ms_per_step_min_median_max": spread(main_res["replay_ms"]),
         "stream_launch_ms_per_step": round(main_res["stream_ms_per_step"], 5),
         "ms_per_step_without_segment_build": round(main_res["nobuild_ms_per_step"], 5),

@@ -326,6 +326,32 @@ int lora_moe_shrink(const lora_pool *pool, int layer, int which, const void *in,
 int lora_moe_expand(const lora_pool *pool, int layer, int which, const lora_segments *seg,
                     void *y0, void *y1, int64_t ldy, void *ws, size_t ws_bytes, void *stream);
 
+/* ------------------------------------------------------------------------------------
+ * Down projection with the routing-weighted combine into token rows.
+ *
+ * Sec. 4.1: a token activates its top-k experts, so rows are pairs p = t * top_k + j;
+ * Sec. 3 / Fig. 7b: the update is added to the base output.  A MoE layer's base output of a
+ * token is the routing-weighted sum of its experts' outputs, so the token row gains
+ *   y_tok[t] += sum over j = 0 .. top_k-1 (ascending) of route_w[t*top_k + j] * delta[t*top_k + j]
+ * with delta the update of the down projection (projection 2) of pair p, over the pairs that
+ * have a valid adapter and expert; a token without such a pair is never read or written.  (The
+ * paper does not spell the routing weights out; with top_k = 1 and route_w = 1 this is
+ * lora_moe_apply(LORA_MOE_DOWN) on token rows.)
+ *
+ * hmid: device bf16 [P][ld_in] per-pair inputs.  adapter_id, expert_id: the device arrays the
+ * segments were built from.  route_w: device fp32 [P].  y_tok: device bf16 [P / top_k][ldy],
+ * updated in place: one fp32 sum in the fixed order above, added to the row in fp32, rounded
+ * to nearest even once; results are bit-identical run to run.  The per-pair updates pass
+ * through bf16 rows inside ws.  ws: device scratch of lora_moe_combine_ws_bytes(pool, P).
+ * seg->P must be a multiple of top_k (1 .. 16).
+ * ------------------------------------------------------------------------------------ */
+size_t lora_moe_combine_ws_bytes(const lora_pool *pool, int P);
+
+int lora_moe_down_combine(const lora_pool *pool, int layer, const void *hmid, int64_t ld_in,
+                          const int32_t *adapter_id, const int32_t *expert_id,
+                          const lora_segments *seg, const float *route_w, int top_k,
+                          void *y_tok, int64_t ldy, void *ws, size_t ws_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -23,7 +23,7 @@ EXPORTED_SYMBOLS = [
     "lora_pool_unit_layout", "lora_pool_device_table", "lora_pool_destroy",
     "lora_segments_ws_bytes", "lora_build_segments", "lora_v_bytes", "lora_shrink",
     "lora_provision_iar", "lora_provision_min_cache", "lora_provision_memory_bytes",
-    "lora_expand", "lora_apply", "lora_group_ws_bytes", "lora_apply_group", "lora_moe_ws_bytes", "lora_moe_apply", "lora_moe_apply_static", "lora_moe_shrink", "lora_moe_expand",
+    "lora_expand", "lora_apply", "lora_group_ws_bytes", "lora_apply_group", "lora_moe_ws_bytes", "lora_moe_apply", "lora_moe_apply_static", "lora_moe_combine_ws_bytes", "lora_moe_down_combine", "lora_moe_shrink", "lora_moe_expand",
 ]
 
 
@@ -135,6 +135,11 @@ def load_library():
     lib.lora_moe_shrink.argtypes = [vp, i32, i32, vp, i64, vp, C.POINTER(_Segments), vp, sz, vp]
     lib.lora_moe_expand.restype = i32
     lib.lora_moe_expand.argtypes = [vp, i32, i32, C.POINTER(_Segments), vp, vp, i64, vp, sz, vp]
+    lib.lora_moe_combine_ws_bytes.restype = sz
+    lib.lora_moe_combine_ws_bytes.argtypes = [vp, i32]
+    lib.lora_moe_down_combine.restype = i32
+    lib.lora_moe_down_combine.argtypes = [vp, i32, vp, i64, vp, vp, C.POINTER(_Segments), vp, i32, vp, i64,
+                                          vp, sz, vp]
     dp = C.POINTER(C.c_double)
     lib.lora_provision_iar.restype = i32
     lib.lora_provision_iar.argtypes = [dp, i32, C.c_double, i32, dp, dp, dp]
@@ -428,6 +433,20 @@ def lora_moe_expand(pool, layer, which, seg: Segments, y0, y1, ldy, ws, ws_bytes
     _check(load_library().lora_moe_expand(_h(pool), layer, which, C.byref(seg.c), _addr(y0),
                                           _addr(y1), ldy, _addr(ws), ws_bytes, _stream(stream)),
            "lora_moe_expand")
+
+
+def lora_moe_combine_ws_bytes(pool, P: int) -> int:
+    return int(load_library().lora_moe_combine_ws_bytes(_h(pool), P))
+
+
+def lora_moe_down_combine(pool, layer, hmid, ld_in, adapter_id, expert_id, seg: Segments, route_w,
+                          top_k, y_tok, ldy, ws, ws_bytes=None, stream=None):
+    if ws_bytes is None:
+        ws_bytes = ws.numel() * ws.element_size()
+    _check(load_library().lora_moe_down_combine(_h(pool), layer, _addr(hmid), ld_in, _addr(adapter_id),
+                                                _addr(expert_id), C.byref(seg.c), _addr(route_w),
+                                                int(top_k), _addr(y_tok), ldy, _addr(ws), ws_bytes,
+                                                _stream(stream)), "lora_moe_down_combine")
 
 
 # ---- cache provisioning (include/lora_provision.h): host arrays in, numbers out ----------------

@@ -290,6 +290,7 @@ struct Group {
     float *v[kMaxFused];
     void *y[kMaxFused];
     int64_t ldy[kMaxFused];
+    int overwrite;           // bf16 decode expand: write the update instead of adding it to y
 };
 
 // bytes of the K parts of one projection's intermediate
@@ -373,6 +374,7 @@ int do_expand(const lora_pool *pool, int layer, const Group &g, const lora_segme
         static const int per_cu = tune_int("LORA_DEC_EXPAND_WGS_PER_CU", 16, 1, 64);
         ep.proj0 = g.proj0;
         ep.n_fused = g.n;
+        ep.overwrite = g.overwrite && out_dtype == LORA_DTYPE_BF16;
         int64_t chunks_per_tile = 0;
         for (int j = 0; j < g.n; ++j) chunks_per_tile += chunks_of(pool->d.proj[g.proj0 + j].h_out);
         const int64_t units = tub * chunks_per_tile;
@@ -1112,6 +1114,70 @@ int lora_moe_apply(const lora_pool *pool, int layer, int which, const void *in, 
     rc = moe_shrink_launch(pool, layer, which, in, ld_in, token_of_pair, seg, ws, st);
     if (rc != LORA_OK) return rc;
     return moe_expand_launch(pool, layer, which, seg, y0, y1, ldy, ws, st);
+}
+
+size_t lora_moe_combine_ws_bytes(const lora_pool *pool, int P)
+{
+    if (check_pool(pool) != LORA_OK || pool->d.n_proj < 3 || P < 0) return 0;
+    const size_t pair_rows = align_up((size_t)std::max(P, 1) * pool->d.proj[2].h_out * sizeof(uint16_t), 256);
+    return align_up(lora_moe_ws_bytes(pool, P), 256) + pair_rows;
+}
+
+int lora_moe_down_combine(const lora_pool *pool, int layer, const void *hmid, int64_t ld_in,
+                          const int32_t *adapter_id, const int32_t *expert_id,
+                          const lora_segments *seg, const float *route_w, int top_k, void *y_tok,
+                          int64_t ldy, void *ws, size_t ws_bytes, void *stream)
+{
+    int rc = check_pool(pool);
+    if (rc != LORA_OK) return rc;
+    rc = check_segments(pool, seg);
+    if (rc != LORA_OK) return rc;
+    const lora_pool_desc &d = pool->d;
+    if (d.n_proj < 3 || layer < 0 || layer >= d.n_layers) return LORA_ERR_BAD_SHAPE;
+    if (top_k < 1 || top_k > combine_max_top_k()) return LORA_ERR_INVALID_ARG;
+    if (seg->P % top_k != 0) return LORA_ERR_BAD_SHAPE;
+    if (seg->P == 0) return LORA_OK;
+    rc = check_act(hmid, ld_in, d.proj[2].h_in, 2);
+    if (rc != LORA_OK) return rc;
+    rc = check_act(y_tok, ldy, d.proj[2].h_out, 2);
+    if (rc != LORA_OK) return rc;
+    if (!adapter_id || !route_w || !ws) return LORA_ERR_INVALID_ARG;
+    if (d.n_experts > 1 && !expert_id) return LORA_ERR_INVALID_ARG;
+    if (!aligned(ws, 16)) return LORA_ERR_MISALIGNED;
+    if (ws_bytes < lora_moe_combine_ws_bytes(pool, seg->P)) return LORA_ERR_BUFFER_TOO_SMALL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int h_out = d.proj[2].h_out;
+    uint16_t *pair = reinterpret_cast<uint16_t *>(static_cast<char *>(ws) +
+                                                  align_up(lora_moe_ws_bytes(pool, seg->P), 256));
+    // 1. shrink of the down projection, as in lora_moe_apply
+    rc = moe_shrink_launch(pool, layer, LORA_MOE_DOWN, hmid, ld_in, nullptr, seg, ws, st);
+    if (rc != LORA_OK) return rc;
+    // 2. the per-pair updates into rows of their own.  Decode batches write them without reading
+    // anything; the long-segment expand only knows how to add, so its rows are cleared first.
+    Group g = moe_group(pool, LORA_MOE_DOWN, seg, ws, pair, nullptr, h_out);
+    if (seg->tile_rows == kDecodeTileRows)
+        g.overwrite = 1;
+    else
+        LORA_HIP(launch_fill_zero(pair, align_up((size_t)seg->P * h_out * sizeof(uint16_t), 16), st));
+    rc = do_expand(pool, layer, g, seg, LORA_DTYPE_BF16, st);
+    if (rc != LORA_OK) return rc;
+    // 3. token rows: y[t] += sum over the token's pairs, ascending, of w * update
+    CombineParams cp;
+    memset(&cp, 0, sizeof cp);
+    cp.pair = pair;
+    cp.ld_pair = h_out;
+    cp.adapter_id = adapter_id;
+    cp.expert_id = d.n_experts > 1 ? expert_id : nullptr;
+    cp.route_w = route_w;
+    cp.T = seg->P / top_k;
+    cp.top_k = top_k;
+    cp.n_adapters = d.n_adapters;
+    cp.n_experts = d.n_experts;
+    cp.h_out = h_out;
+    cp.y = static_cast<uint16_t *>(y_tok);
+    cp.ldy = ldy;
+    LORA_HIP(launch_combine(cp, st));
+    return LORA_OK;
 }
 
 }  // extern "C"

@@ -28,7 +28,9 @@ namespace lora {
 
 namespace {
 
-template <int R, bool F32, int NI>
+// OVW: the output rows are written, not updated: the base output counts as zero and is never
+// read (used when the update goes to a buffer of its own rather than into base rows).
+template <int R, bool F32, int NI, bool OVW>
 struct ExpandWave {
     using Tile = ExpandTile<R>;
     static constexpr int KS = Tile::KS;
@@ -53,7 +55,8 @@ struct ExpandWave {
 #pragma unroll
         for (int i = 0; i < NI; ++i)
 #pragma unroll
-            for (int q = 0; q < NY; ++q) y.r[i][q] = ld16<false>(yrow[i] + (int64_t)colc * ESZ + 16 * q);
+            for (int q = 0; q < NY; ++q)
+                y.r[i][q] = OVW ? u32x4{0u, 0u, 0u, 0u} : ld16<false>(yrow[i] + (int64_t)colc * ESZ + 16 * q);
     }
 
     __device__ inline void compute_store(int c, const typename Tile::B &b, const YBuf &y) const
@@ -126,13 +129,13 @@ struct ExpandWave {
     }
 };
 
-template <int R, bool F32, int NI>
+template <int R, bool F32, int NI, bool OVW>
 __device__ inline void expand_item(const ExpandParams &p, const lora_tile &t, const Unit &unit, int pj,
                                    int c0, int c1, int lane)
 {
     using Tile = ExpandTile<R>;
     constexpr int KS = Tile::KS, KV = Tile::KV, ESZ = F32 ? 4 : 2;
-    ExpandWave<R, F32, NI> w;
+    ExpandWave<R, F32, NI, OVW> w;
     w.lane = lane;
     w.g = lane >> 4;
     w.i16 = lane & 15;
@@ -148,7 +151,7 @@ __device__ inline void expand_item(const ExpandParams &p, const lora_tile &t, co
     }
 
     // the first chunks' weights and base output: in flight while v is fetched
-    typename ExpandWave<R, F32, NI>::Stage st[ExpandWave<R, F32, NI>::D];
+    typename ExpandWave<R, F32, NI, OVW>::Stage st[ExpandWave<R, F32, NI, OVW>::D];
     w.prefetch(c0, c1, st);
 
     // v operand: this lane's row slot i16 holds tile row (i16 % 4) * 4 + i16 / 4
@@ -182,7 +185,7 @@ __device__ inline void expand_item(const ExpandParams &p, const lora_tile &t, co
 // tiles, units and counts are passed again as restrict-qualified kernel arguments: with a
 // wave-uniform index the compiler then reads them through the scalar cache, which shortens
 // the dependent chain tile -> unit -> first data load.
-template <int R, bool F32>
+template <int R, bool F32, bool OVW>
 __global__ __launch_bounds__(256, 2) void expand16_kernel(ExpandParams p,
                                                           const lora_tile *__restrict__ tiles,
                                                           const Unit *__restrict__ units,
@@ -214,10 +217,10 @@ __global__ __launch_bounds__(256, 2) void expand16_kernel(ExpandParams p,
         const lora_tile t = tiles[tile_ix];
         const Unit unit = units[(int64_t)t.key * p.n_proj + p.proj0 + pj];
         switch ((t.n_rows + 3) >> 2) {              // wave-uniform
-        case 1: expand_item<R, F32, 1>(p, t, unit, pj, c0, c1, lane); break;
-        case 2: expand_item<R, F32, 2>(p, t, unit, pj, c0, c1, lane); break;
-        case 3: expand_item<R, F32, 3>(p, t, unit, pj, c0, c1, lane); break;
-        default: expand_item<R, F32, 4>(p, t, unit, pj, c0, c1, lane); break;
+        case 1: expand_item<R, F32, 1, OVW>(p, t, unit, pj, c0, c1, lane); break;
+        case 2: expand_item<R, F32, 2, OVW>(p, t, unit, pj, c0, c1, lane); break;
+        case 3: expand_item<R, F32, 3, OVW>(p, t, unit, pj, c0, c1, lane); break;
+        default: expand_item<R, F32, 4, OVW>(p, t, unit, pj, c0, c1, lane); break;
         }
     }
 }
@@ -227,9 +230,11 @@ hipError_t launch_r(const ExpandParams &p, hipStream_t s)
 {
     const dim3 block(p.waves * 64);
     if (p.out_f32)
-        hipLaunchKernelGGL((expand16_kernel<R, true>), dim3(p.grid), block, 0, s, p, p.tiles, p.units, p.counts);
+        hipLaunchKernelGGL((expand16_kernel<R, true, false>), dim3(p.grid), block, 0, s, p, p.tiles, p.units, p.counts);
+    else if (p.overwrite)
+        hipLaunchKernelGGL((expand16_kernel<R, false, true>), dim3(p.grid), block, 0, s, p, p.tiles, p.units, p.counts);
     else
-        hipLaunchKernelGGL((expand16_kernel<R, false>), dim3(p.grid), block, 0, s, p, p.tiles, p.units, p.counts);
+        hipLaunchKernelGGL((expand16_kernel<R, false, false>), dim3(p.grid), block, 0, s, p, p.tiles, p.units, p.counts);
     return hipGetLastError();
 }
 

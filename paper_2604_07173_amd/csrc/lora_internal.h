@@ -116,8 +116,23 @@ struct ExpandParams {
     int waves;               // waves per workgroup
     int tile_group;          // decode kernel: consecutive wave items walk over this many tiles
     int out_f32;
+    int overwrite;           // decode kernel, bf16 output: write the update, do not read the rows
     int rank;
     int grid;
+};
+
+// routing-weighted combine of per-pair update rows into token rows
+struct CombineParams {
+    const uint16_t *pair;    // bf16 [P][ld_pair] per-pair updates (rows of inactive pairs unspecified)
+    int64_t ld_pair;
+    const int32_t *adapter_id;
+    const int32_t *expert_id;
+    const float *route_w;    // [P]
+    int T, top_k;
+    int n_adapters, n_experts;
+    int h_out;
+    uint16_t *y;             // bf16 [T][ldy] token rows, updated in place
+    int64_t ldy;
 };
 
 hipError_t launch_pack_A(const PackParams &p, hipStream_t s);
@@ -135,5 +150,8 @@ size_t expand_image_bytes(int rank, int64_t n_tiles);   // operand images of n_t
 int expand_long_group();                                 // tiles per wave item of launch_expand
 hipError_t launch_shrink_decode(const ShrinkParams &p, hipStream_t s);   // tiles of <= 16 rows
 hipError_t launch_expand_decode(const ExpandParams &p, hipStream_t s);
+hipError_t launch_combine(const CombineParams &p, hipStream_t s);
+int combine_max_top_k();
+hipError_t launch_fill_zero(void *dst, size_t bytes, hipStream_t s);      // bytes a multiple of 16
 
 }  // namespace lora
