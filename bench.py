@@ -121,6 +121,18 @@ def make_phases(L, W, dp, db, run, acct, down_combine=False):
     return phases
 
 
+def launches_per_step(w, dp, db, run):
+    """How many kernel launches one step takes: 1 for the segment build, then per group of
+    projections 1 if the library runs shrink and expand as one launch, else 2 (3 for batches of
+    long segments, whose expand has a launch of its own for the operand images)."""
+    import paper_2604_07173_amd as L
+    one = getattr(L, "lora_group_launches", None)
+    if one is None:
+        return None
+    groups = [(0, 2), (2, 1)] if w.kind == "moe" else run.groups
+    return 1 + sum(L.lora_group_launches(dp.pool, j, c, db.P, db.seg) for j, c in groups)
+
+
 def measure(name, args, steps, warmup, with_cpu_baseline):
     import numpy as np
     import torch
@@ -139,15 +151,25 @@ def measure(name, args, steps, warmup, with_cpu_baseline):
     acct = W.algorithmic_bytes(w, b.adapter_id, b.expert_id)
     phases = make_phases(L, W, dp, db, run, acct, getattr(args, "down_combine", False) and w.kind == "moe")
 
+    combine = getattr(args, "down_combine", False) and w.kind == "moe"
+
     def step(it):
+        # the calls a server makes for one layer: lora_build_segments, then lora_moe_apply for
+        # up/gate and for down (MoE) or lora_apply_group per run of projections that share an
+        # input (dense).  The library decides by itself whether shrink and expand of a group run
+        # as one launch or two; the phases below time the two halves on their own.
         layer = it % n_layers
-        for ph in phases:
-            ph.fn(layer)
+        if combine:
+            for ph in phases:
+                ph.fn(layer)
+        else:
+            run.step(layer)
 
     # ---- whole-step throughput ----------------------------------------------------------
     for it in range(warmup):
         step(it)
     torch.cuda.synchronize()
+    launches = launches_per_step(w, dp, db, run)      # the segments are built by now
     t0 = time.perf_counter()
     for it in range(steps):
         step(warmup + it)
@@ -271,7 +293,8 @@ def measure(name, args, steps, warmup, with_cpu_baseline):
         two_calls=dict(ms_per_step=two_ms_per_step, tokens_per_s=w.tokens / (two_ms_per_step * 1e-3),
                        hbm_frac_of_peak=(total_bytes + bytes2) / 2 / (two_ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS),
         algorithmic_bytes=int(total_bytes), segments=acct["S"], pairs=acct["P_act"],
-        layers_in_pool=n_layers, pool_gib=dp.nbytes / 2 ** 30, phases=per_phase, roofline=roofline)
+        layers_in_pool=n_layers, pool_gib=dp.nbytes / 2 ** 30, phases=per_phase, roofline=roofline,
+        launches_per_step=launches)
 
     if with_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(w, b, ws)
@@ -508,6 +531,7 @@ def main():
         "copy_ceiling_gbs": round(ceiling, 1),
         "hbm_frac_of_copy_ceiling": round(main_res["step_gbs"] / ceiling, 4),
         "algorithmic_bytes_per_step": main_res["algorithmic_bytes"],
+        "launches_per_step": main_res["launches_per_step"],
         "pairs_per_s": round(main_res["pairs_per_s"], 1),
         "phases": {k: {"us": round(v["us"], 2), "GB/s": round(v["gbs"], 1)}
                    for k, v in main_res["phases"].items()},
@@ -533,6 +557,7 @@ def main():
                            "hbm_gbs": round(r["step_gbs"], 1),
                            "hbm_frac_of_peak": round(r["step_frac_of_peak"], 4),
                            "algorithmic_bytes_per_step": r["algorithmic_bytes"],
+                           "launches_per_step": r["launches_per_step"],
                            "graph_replays_ms_per_step_min_median_max": spread(r["replay_ms"]),
                            "two_calls_in_flight_ms_per_step":
                                None if args.no_two_calls else round(r["two_calls"]["ms_per_step"], 5),

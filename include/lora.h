@@ -267,6 +267,14 @@ int lora_apply(const lora_pool *pool, int layer, int proj, const void *x, int64_
  */
 size_t lora_group_ws_bytes(const lora_pool *pool, int proj0, int n_proj, int P);
 
+/* How many kernel launches lora_apply_group (lora_apply: n_proj = 1; lora_moe_apply: up/gate is
+ * proj0 = 0, n_proj = 2, down is proj0 = 2, n_proj = 1) enqueues for these segments: 1 when shrink
+ * and expand run as one launch (small decode batches with short inputs), else 2 or more; 0 for an empty
+ * batch; a negative lora_status on a bad argument.  A host-side query for schedulers and
+ * benchmarks; it enqueues nothing. */
+int lora_group_launches(const lora_pool *pool, int proj0, int n_proj, int out_dtype,
+                        const lora_segments *seg);
+
 int lora_apply_group(const lora_pool *pool, int layer, int proj0, int n_proj, const void *x,
                      int64_t ldx, const int32_t *src_row, const lora_segments *seg,
                      void *const *y, const int64_t *ldy, int out_dtype, void *ws,

@@ -23,7 +23,7 @@ EXPORTED_SYMBOLS = [
     "lora_pool_unit_layout", "lora_pool_device_table", "lora_pool_destroy",
     "lora_segments_ws_bytes", "lora_build_segments", "lora_v_bytes", "lora_shrink",
     "lora_provision_iar", "lora_provision_min_cache", "lora_provision_memory_bytes",
-    "lora_expand", "lora_apply", "lora_group_ws_bytes", "lora_apply_group", "lora_moe_ws_bytes", "lora_moe_apply", "lora_moe_apply_static", "lora_moe_combine_ws_bytes", "lora_moe_down_combine", "lora_moe_shrink", "lora_moe_expand",
+    "lora_expand", "lora_apply", "lora_group_ws_bytes", "lora_group_launches", "lora_apply_group", "lora_moe_ws_bytes", "lora_moe_apply", "lora_moe_apply_static", "lora_moe_combine_ws_bytes", "lora_moe_down_combine", "lora_moe_shrink", "lora_moe_expand",
 ]
 
 
@@ -121,6 +121,8 @@ def load_library():
     lib.lora_apply.argtypes = [vp, i32, i32, vp, i64, vp, C.POINTER(_Segments), vp, i64, i32, vp, vp]
     lib.lora_group_ws_bytes.restype = sz
     lib.lora_group_ws_bytes.argtypes = [vp, i32, i32, i32]
+    lib.lora_group_launches.restype = i32
+    lib.lora_group_launches.argtypes = [vp, i32, i32, i32, C.POINTER(_Segments)]
     lib.lora_apply_group.restype = i32
     lib.lora_apply_group.argtypes = [vp, i32, i32, i32, vp, i64, vp, C.POINTER(_Segments),
                                      C.POINTER(vp), C.POINTER(i64), i32, vp, sz, vp]
@@ -381,6 +383,15 @@ def lora_apply(pool, layer, proj, x, ldx, src_row, seg: Segments, y, ldy, v,
 
 def lora_group_ws_bytes(pool, proj0: int, n_proj: int, P: int) -> int:
     return int(load_library().lora_group_ws_bytes(_h(pool), proj0, n_proj, P))
+
+
+def lora_group_launches(pool, proj0: int, n_proj: int, P: int, seg: Segments,
+                        out_dtype=LORA_DTYPE_BF16) -> int:
+    """Kernel launches lora_apply_group would enqueue for this group and these (built) segments."""
+    rc = load_library().lora_group_launches(_h(pool), proj0, n_proj, out_dtype, C.byref(seg.c))
+    if rc < 0:
+        _check(rc, "lora_group_launches")
+    return rc
 
 
 def lora_apply_group(pool, layer, proj0, x, ldx, src_row, seg: Segments, ys, ldys, ws,

@@ -10,8 +10,8 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "liblora.so")
 SOURCES = ["api.hip", "pack.hip", "segments.hip", "shrink.hip", "expand.hip",
-           "shrink_decode.hip", "expand_decode.hip", "combine.hip", "provision.cpp"]
-HEADERS = ["lora_internal.h", "lora_layout.h", "lora_device.h", "expand_common.h", os.path.join("..", "..", "include", "lora.h"),
+           "shrink_decode.hip", "expand_decode.hip", "fused_decode.hip", "combine.hip", "provision.cpp"]
+HEADERS = ["lora_internal.h", "lora_layout.h", "lora_device.h", "expand_common.h", "expand_item.h", "shrink_wave.h", os.path.join("..", "..", "include", "lora.h"),
            os.path.join("..", "..", "include", "lora_provision.h")]
 
 HIPCC_FLAGS = [
@@ -40,10 +40,14 @@ def is_stale() -> bool:
     return any(os.path.getmtime(d) > t for d in deps)
 
 
-def build(verbose: bool = False, jobs: int = 7) -> str:
-    """Compile every translation unit and link the shared library. Always compiles."""
+def build(verbose: bool = False, jobs: int = 7, extra_flags=(), out: str = LIB_PATH) -> str:
+    """Compile every translation unit and link the shared library. Always compiles.
+
+    extra_flags / out: a second build of the library next to the installed one, e.g.
+    extra_flags=("-DLORA_TUNING",) for a build whose work-split constants can be set from the
+    environment during parameter sweeps."""
     cc = hipcc()
-    objdir = os.path.join(PKG_DIR, "_build")
+    objdir = os.path.join(PKG_DIR, "_build" if out == LIB_PATH else "_build_" + os.path.basename(out))
     os.makedirs(objdir, exist_ok=True)
     procs = []
     objs = []
@@ -51,16 +55,16 @@ def build(verbose: bool = False, jobs: int = 7) -> str:
         obj = os.path.join(objdir, os.path.splitext(src)[0] + ".o")
         objs.append(obj)
         flags = HIPCC_FLAGS if src.endswith(".hip") else HOST_FLAGS
-        cmd = [cc, *flags, "-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [cc, *flags, *extra_flags, "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT)))
         if len(procs) >= jobs:
             _drain(procs)
     _drain(procs)
-    cmd = [cc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB_PATH, *objs]
+    cmd = [cc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", out, *objs]
     subprocess.check_call(cmd)
-    return LIB_PATH
+    return out
 
 
 def _drain(procs):
@@ -77,4 +81,7 @@ def _drain(procs):
 
 
 if __name__ == "__main__":
-    print(build(verbose=True))
+    if len(sys.argv) > 1 and sys.argv[1] == "--tuning":       # python -m ...build --tuning OUT.so
+        print(build(verbose=True, extra_flags=("-DLORA_TUNING",), out=os.path.abspath(sys.argv[2])))
+    else:
+        print(build(verbose=True))

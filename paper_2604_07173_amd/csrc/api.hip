@@ -299,8 +299,10 @@ size_t parts_bytes(const lora_pool *pool, int n_parts, int P)
     return align_up((size_t)n_parts * std::max(P, 1) * pool->d.rank * sizeof(float), 256);
 }
 
-int do_shrink(const lora_pool *pool, int layer, const Group &g, const void *x, int64_t ldx,
-              const int32_t *src_row, const lora_segments *seg, hipStream_t st)
+// launch parameters of the shrink of a group (decode kernels: complete; long kernels: all but
+// the per-launch projection fields)
+ShrinkParams shrink_params(const lora_pool *pool, int layer, const Group &g, const void *x, int64_t ldx,
+                           const int32_t *src_row, const lora_segments *seg)
 {
     const lora_proj_desc &pd = pool->d.proj[g.proj0];
     const KSplit ks = ksplit_of(pool, g.proj0, seg->P);
@@ -328,14 +330,24 @@ int do_shrink(const lora_pool *pool, int layer, const Group &g, const void *x, i
         sp.wave_per_tile = ks.wave_per_tile;
         const int64_t wgs = ks.wave_per_tile ? (items + 3) / 4 : items;
         sp.grid = (int)std::min<int64_t>(wgs, (int64_t)cu_count() * per_cu);
-        LORA_HIP(launch_shrink_decode(sp, st));
-        return LORA_OK;
+        return sp;
     }
     // 32-row tiles: work items are groups of tiles; at most two projections per launch
     static const int per_cu = tune_int("LORA_SHRINK_WGS_PER_CU", 2, 1, 64);
     const int64_t groups = (tiles_upper_bound(pool, seg->P, seg->tile_rows) + shrink_long_tiles() - 1) /
                            shrink_long_tiles();
     sp.grid = (int)std::min<int64_t>(groups * ks.n_parts, (int64_t)cu_count() * per_cu);
+    return sp;
+}
+
+int do_shrink(const lora_pool *pool, int layer, const Group &g, const void *x, int64_t ldx,
+              const int32_t *src_row, const lora_segments *seg, hipStream_t st)
+{
+    ShrinkParams sp = shrink_params(pool, layer, g, x, ldx, src_row, seg);
+    if (seg->tile_rows == kDecodeTileRows) {
+        LORA_HIP(launch_shrink_decode(sp, st));
+        return LORA_OK;
+    }
     for (int j = 0; j < g.n; j += 2) {
         sp.proj0 = g.proj0 + j;
         sp.n_fused = std::min(2, g.n - j);
@@ -346,11 +358,26 @@ int do_shrink(const lora_pool *pool, int layer, const Group &g, const void *x, i
     return LORA_OK;
 }
 
+int expand_params(const lora_pool *pool, int layer, const Group &g, const lora_segments *seg,
+                  int out_dtype, ExpandParams &ep);
+
 int do_expand(const lora_pool *pool, int layer, const Group &g, const lora_segments *seg,
               int out_dtype, hipStream_t st)
 {
-    const KSplit ks = ksplit_of(pool, g.proj0, seg->P);
     ExpandParams ep;
+    expand_params(pool, layer, g, seg, out_dtype, ep);
+    if (seg->tile_rows == kDecodeTileRows)
+        LORA_HIP(launch_expand_decode(ep, st));
+    else
+        LORA_HIP(launch_expand(ep, st));
+    return LORA_OK;
+}
+
+// launch parameters of the expand of a group
+int expand_params(const lora_pool *pool, int layer, const Group &g, const lora_segments *seg,
+                  int out_dtype, ExpandParams &ep)
+{
+    const KSplit ks = ksplit_of(pool, g.proj0, seg->P);
     memset(&ep, 0, sizeof ep);
     ep.units = pool->device_table() + pool->table_index(layer, 0, 0, 0);
     ep.n_proj = pool->d.n_proj;
@@ -413,7 +440,6 @@ int do_expand(const lora_pool *pool, int layer, const Group &g, const lora_segme
         const int64_t wave_items = (tub + ep.tile_group - 1) / ep.tile_group * ep.tile_group * ep.slice0[g.n];
         ep.grid = (int)std::min<int64_t>((wave_items + ep.waves - 1) / ep.waves,
                                          (int64_t)cu_count() * per_cu);
-        LORA_HIP(launch_expand_decode(ep, st));
         return LORA_OK;
     }
     // long segments: operand images of the sub-tiles behind the K parts in each projection's
@@ -438,8 +464,76 @@ int do_expand(const lora_pool *pool, int layer, const Group &g, const lora_segme
     const int64_t wave_items = groups * ep.slice0[g.n];
     ep.grid = (int)std::min<int64_t>((wave_items + 3) / 4, (int64_t)cu_count() * per_cu);
     ep.image_grid = (int)std::min<int64_t>((tub * 2 * g.n + 3) / 4, (int64_t)cu_count() * 8);
-    LORA_HIP(launch_expand(ep, st));
     return LORA_OK;
+}
+
+// Shrink and expand of a group as one launch (fused_decode.hip): every workgroup repeats the
+// shrink of its tile and projection and expands a slice of the output columns, so the launch
+// needs no hand-off between workgroups but reads A once per slice (from the L2 after the first).
+// Worth it only for small decode batches with short inputs: few tiles (the repeated reads stay
+// small against the bytes of B and y, and a second launch would cost more than it moves) and a
+// K range that four waves get through quickly.  Returns false if the group is not eligible;
+// otherwise fills the slicing of ep (n_slices, cps, slice0) and the grid.
+bool fused_plan(const lora_pool *pool, const Group &g, const lora_segments *seg, int out_dtype,
+                ShrinkParams *sp, ExpandParams *ep)
+{
+    static const int enabled = tune_int("LORA_FUSED", 1, 0, 1);
+    static const int max_k = tune_int("LORA_FUSED_MAX_K", kFusedMaxK, 8, 1 << 20);
+    static const int max_tiles = tune_int("LORA_FUSED_MAX_TILES", kFusedMaxTiles, 1, 1 << 20);
+    static const int min_chunks = tune_int("LORA_FUSED_MIN_CHUNKS", kFusedMinChunks, 1, 1 << 20);
+    static const int want_wgs = tune_int("LORA_FUSED_WGS", kFusedWorkgroups, 1, 1 << 20);
+    if (!enabled || seg->tile_rows != kDecodeTileRows || out_dtype != LORA_DTYPE_BF16 || g.overwrite)
+        return false;
+    if (pool->d.proj[g.proj0].h_in > max_k) return false;
+    {
+        static const int max_chunks = tune_int("LORA_FUSED_MAX_CHUNKS", kFusedMaxChunks, 1, 1 << 20);
+        int chunks = 0;
+        for (int j = 0; j < g.n; ++j) chunks += chunks_of(pool->d.proj[g.proj0 + j].h_out);
+        if (chunks > max_chunks) return false;
+    }
+    const int64_t tub = std::max<int64_t>(1, tiles_upper_bound(pool, seg->P, kDecodeTileRows));
+    if (tub > max_tiles) return false;
+    if (!sp || !ep) return true;
+    // slices per projection: enough workgroups to occupy the chip, but at least min_chunks
+    // chunks per slice (a workgroup repeats a whole shrink for them)
+    int total_chunks = 0;
+    for (int j = 0; j < g.n; ++j) total_chunks += chunks_of(pool->d.proj[g.proj0 + j].h_out);
+    const double per_tile = std::max(1.0, (double)want_wgs / (double)tub);
+    ep->slice0[0] = 0;
+    for (int j = 0; j < g.n; ++j) {
+        const int n = chunks_of(pool->d.proj[g.proj0 + j].h_out);
+        int slices = (int)std::lround(per_tile * n / total_chunks);
+        slices = std::max(1, std::min(slices, std::max(1, n / min_chunks)));
+        int cps = (n + slices - 1) / slices;
+        cps = std::min(n, (cps + 1) & ~1);                      // even: two chunks are in flight
+        ep->cps[j] = cps;
+        ep->n_slices[j] = (n + cps - 1) / cps;
+        ep->slice0[j + 1] = ep->slice0[j] + ep->n_slices[j];
+    }
+    for (int j = g.n; j < kMaxFused; ++j) ep->slice0[j + 1] = ep->slice0[g.n];
+    sp->n_parts = 1;
+    sp->kb_per_part = kblocks_of(pool->d.proj[g.proj0].h_in, pool->d.rank);
+    ep->n_parts = 1;
+    sp->grid = (int)std::min<int64_t>(tub * ep->slice0[g.n], (int64_t)cu_count() * 8);
+    return true;
+}
+
+// shrink then expand of a group: one launch where that is possible, else two
+int do_apply(const lora_pool *pool, int layer, const Group &g, const void *x, int64_t ldx,
+             const int32_t *src_row, const lora_segments *seg, int out_dtype, hipStream_t st)
+{
+    if (fused_plan(pool, g, seg, out_dtype, nullptr, nullptr)) {
+        FusedParams fp;
+        memset(&fp, 0, sizeof fp);
+        fp.s = shrink_params(pool, layer, g, x, ldx, src_row, seg);
+        expand_params(pool, layer, g, seg, out_dtype, fp.e);
+        fused_plan(pool, g, seg, out_dtype, &fp.s, &fp.e);
+        LORA_HIP(launch_fused_decode(fp, st));
+        return LORA_OK;
+    }
+    int rc = do_shrink(pool, layer, g, x, ldx, src_row, seg, st);
+    if (rc != LORA_OK) return rc;
+    return do_expand(pool, layer, g, seg, out_dtype, st);
 }
 
 Group single(int proj, float *v, void *y, int64_t ldy)
@@ -920,10 +1014,7 @@ int lora_apply(const lora_pool *pool, int layer, int proj, const void *x, int64_
     if (!v) return LORA_ERR_INVALID_ARG;
     if (!aligned(v, 16)) return LORA_ERR_MISALIGNED;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const Group g = single(proj, v, y, ldy);
-    rc = do_shrink(pool, layer, g, x, ldx, src_row, seg, st);
-    if (rc != LORA_OK) return rc;
-    return do_expand(pool, layer, g, seg, out_dtype, st);
+    return do_apply(pool, layer, single(proj, v, y, ldy), x, ldx, src_row, seg, out_dtype, st);
 }
 
 size_t lora_group_ws_bytes(const lora_pool *pool, int proj0, int n_proj, int P)
@@ -967,10 +1058,25 @@ int lora_apply_group(const lora_pool *pool, int layer, int proj0, int n_proj, co
         g.y[j] = y[j];
         g.ldy[j] = ldy[j];
     }
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    rc = do_shrink(pool, layer, g, x, ldx, src_row, seg, st);
+    return do_apply(pool, layer, g, x, ldx, src_row, seg, out_dtype, static_cast<hipStream_t>(stream));
+}
+
+int lora_group_launches(const lora_pool *pool, int proj0, int n_proj, int out_dtype,
+                        const lora_segments *seg)
+{
+    int rc = check_pool(pool);
     if (rc != LORA_OK) return rc;
-    return do_expand(pool, layer, g, seg, out_dtype, st);
+    rc = check_segments(pool, seg);
+    if (rc != LORA_OK) return rc;
+    if (n_proj < 1 || n_proj > kMaxFused || proj0 < 0 || proj0 + n_proj > pool->d.n_proj)
+        return LORA_ERR_BAD_SHAPE;
+    if (seg->P == 0) return 0;
+    Group g;
+    memset(&g, 0, sizeof g);
+    g.proj0 = proj0;
+    g.n = n_proj;
+    if (seg->tile_rows == kDecodeTileRows) return fused_plan(pool, g, seg, out_dtype, nullptr, nullptr) ? 1 : 2;
+    return (n_proj + 1) / 2 + 2;       // long segments: shrink launches of two projections, images, expand
 }
 
 size_t lora_moe_ws_bytes(const lora_pool *pool, int P)
@@ -1110,10 +1216,9 @@ int lora_moe_apply(const lora_pool *pool, int layer, int which, const void *in, 
     if (rc != LORA_OK) return rc;
     rc = moe_expand_checks(pool, which, y0, y1, ldy);
     if (rc != LORA_OK) return rc;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    rc = moe_shrink_launch(pool, layer, which, in, ld_in, token_of_pair, seg, ws, st);
-    if (rc != LORA_OK) return rc;
-    return moe_expand_launch(pool, layer, which, seg, y0, y1, ldy, ws, st);
+    return do_apply(pool, layer, moe_group(pool, which, seg, ws, y0, y1, ldy), in, ld_in,
+                    which == LORA_MOE_UPGATE ? token_of_pair : nullptr, seg, LORA_DTYPE_BF16,
+                    static_cast<hipStream_t>(stream));
 }
 
 size_t lora_moe_combine_ws_bytes(const lora_pool *pool, int P)

@@ -26,6 +26,16 @@ constexpr int kKBlock = 32;          // K elements per MFMA step (v_mfma_f32_16x
 constexpr int kColChunk = 128;       // output columns one wave owns in expand
 constexpr int kPartKBlocks = 32;     // K-blocks one shrink workgroup reduces (1024 inputs)
 constexpr int kMaxParts = 64;
+// Shrink and expand in one launch (fused_decode.hip): limits and work split, measured on MI355X
+// with the Llama-3-8B query/key/value and output projections (rank 16, 4096 inputs): one launch
+// takes 10.3-10.5 us against 13.2-14.1 us for two up to 27 tiles, 12.7 against 14.2 at 41 tiles,
+// and the two are equal at 54 tiles; wide outputs (gate and up, 224 chunks) and long inputs
+// (down, 14336) are slower in one launch at every size.
+constexpr int kFusedMaxK = 4096;       // longest input
+constexpr int kFusedMaxChunks = 64;    // widest group, in 128-column chunks per tile
+constexpr int kFusedMaxTiles = 64;     // largest batch, as the host's upper bound of the tile count
+constexpr int kFusedMinChunks = 16;    // 128-column chunks a workgroup expands at least
+constexpr int kFusedWorkgroups = 1024; // workgroups aimed at
 constexpr int kMaxFused = 3;         // projections that share an input in one launch (q/k/v, gate/up)
 
 // ---- packed layout sizes ---------------------------------------------------------------
@@ -135,6 +145,12 @@ struct CombineParams {
     int64_t ldy;
 };
 
+// shrink and expand of a decode batch in one launch
+struct FusedParams {
+    ShrinkParams s;          // n_parts = 1; v unused
+    ExpandParams e;          // n_slices / cps / slice0: workgroup items of a tile; v unused
+};
+
 hipError_t launch_pack_A(const PackParams &p, hipStream_t s);
 hipError_t launch_pack_B(const PackParams &p, hipStream_t s);
 hipError_t launch_pack_layer(const PackLayerParams &p, hipStream_t s);
@@ -150,6 +166,7 @@ size_t expand_image_bytes(int rank, int64_t n_tiles);   // operand images of n_t
 int expand_long_group();                                 // tiles per wave item of launch_expand
 hipError_t launch_shrink_decode(const ShrinkParams &p, hipStream_t s);   // tiles of <= 16 rows
 hipError_t launch_expand_decode(const ExpandParams &p, hipStream_t s);
+hipError_t launch_fused_decode(const FusedParams &p, hipStream_t s);
 hipError_t launch_combine(const CombineParams &p, hipStream_t s);
 int combine_max_top_k();
 hipError_t launch_fill_zero(void *dst, size_t bytes, hipStream_t s);      // bytes a multiple of 16

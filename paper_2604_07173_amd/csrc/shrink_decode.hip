@@ -16,105 +16,11 @@
 // Rank 8: a packed block holds 64 K values (two 32-deep halves side by side in the 16 M
 // rows), is multiplied once with each half's x values, and rows 0..7 of the first product
 // plus rows 8..15 of the second give the eight rank entries.
-#include "lora_device.h"
-#include "lora_internal.h"
+#include "shrink_wave.h"
 
 namespace lora {
 
 namespace {
-
-template <int R, int NPROJ, bool NT>
-struct ShrinkWave {
-    static constexpr int NB = R >= 16 ? R / 16 : 1;            // weight tiles per K unit
-    static constexpr int XN = R == 8 ? 2 : 1;                  // x operands per K unit
-    static constexpr int NACC = R == 8 ? 2 : NB;               // accumulators per projection
-    static constexpr int KU = R == 8 ? 64 : 32;                // K values per unit
-    static constexpr int KB = R <= 16 ? (R == 8 ? 2 : 4) : (R == 32 ? 2 : 1);   // units per step
-
-    int lane, g, i16, h_in;
-    const uint16_t *Ap[NPROJ];
-    const uint16_t *xp;      // this lane's x row (a valid row even if the lane's row is not)
-    bool row_ok;
-    f32x4 acc[NPROJ][NACC];
-
-    struct Step {
-        u32x4 w[NPROJ][KB][NB];
-        u32x4 x[KB][XN];
-    };
-
-    // All loads are unconditional: a K unit beyond the wave's range re-reads the last valid
-    // unit and a row beyond the tile re-reads the tile's first row; both are then replaced
-    // by zeros with selects.  No branches, so the next step's loads stay in flight.
-    __device__ inline void load(int kb0, int kb_end, Step &s) const
-    {
-        const u32x4 zero4 = {0u, 0u, 0u, 0u};
-#pragma unroll
-        for (int u = 0; u < KB; ++u) {
-            const bool k_ok = kb0 + u < kb_end;
-            const int kb = k_ok ? kb0 + u : kb_end - 1;
-#pragma unroll
-            for (int pj = 0; pj < NPROJ; ++pj)
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb) {
-                    const u32x4 t = ld16<NT>(Ap[pj] + (((int64_t)kb * NB + nb) * 64 + lane) * 8);
-                    s.w[pj][u][nb] = k_ok ? t : zero4;
-                }
-#pragma unroll
-            for (int h = 0; h < XN; ++h) {
-                const int c = kb * KU + h * 32 + g * 8;
-                const bool c_ok = c < h_in;
-                const u32x4 t = ld16<false>(xp + (c_ok ? c : 0));
-                s.x[u][h] = (k_ok && row_ok && c_ok) ? t : zero4;
-            }
-        }
-    }
-
-    __device__ inline void mma(const Step &s)
-    {
-#pragma unroll
-        for (int u = 0; u < KB; ++u)
-#pragma unroll
-            for (int pj = 0; pj < NPROJ; ++pj) {
-                if (R == 8) {
-#pragma unroll
-                    for (int h = 0; h < 2; ++h)
-                        acc[pj][h] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                            as_bf16x8(s.w[pj][u][0]), as_bf16x8(s.x[u][h]), acc[pj][h], 0, 0, 0);
-                } else {
-#pragma unroll
-                    for (int nb = 0; nb < NB; ++nb)
-                        acc[pj][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                            as_bf16x8(s.w[pj][u][nb]), as_bf16x8(s.x[u][0]), acc[pj][nb], 0, 0, 0);
-                }
-            }
-    }
-
-    // K units [kb_begin, kb_end), two steps in flight
-    __device__ inline void run(int kb_begin, int kb_end)
-    {
-#pragma unroll
-        for (int pj = 0; pj < NPROJ; ++pj)
-#pragma unroll
-            for (int a = 0; a < NACC; ++a) acc[pj][a] = f32x4{0.f, 0.f, 0.f, 0.f};
-        if (kb_begin >= kb_end) return;
-        Step s0, s1;
-        load(kb_begin, kb_end, s0);
-        int kb0 = kb_begin;
-        for (; kb0 + 2 * KB < kb_end; kb0 += 2 * KB) {
-            load(kb0 + KB, kb_end, s1);
-            mma(s0);
-            load(kb0 + 2 * KB, kb_end, s0);
-            mma(s1);
-        }
-        if (kb0 + KB < kb_end) {
-            load(kb0 + KB, kb_end, s1);
-            mma(s0);
-            mma(s1);
-        } else {
-            mma(s0);
-        }
-    }
-};
 
 // tiles, units and counts are passed again as restrict-qualified kernel arguments: with a
 // uniform index the compiler then reads them through the scalar cache, which shortens the

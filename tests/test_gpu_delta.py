@@ -6,7 +6,7 @@ import torch
 
 import paper_2604_07173_amd as L
 import workloads as W
-from gpu_common import check_accumulate, check_delta, oracle_projection
+from gpu_common import bf16_ulp, check_accumulate, check_delta, oracle_projection
 from harness import DeviceBatch, DevicePool, LayerRunner, bits_from_dev, to_dev
 
 pytestmark = pytest.mark.gpu
@@ -43,6 +43,18 @@ def run_dense(w, seed, y_mode, out_f32=False, drop=0.0, hetero=True, n_layers=1,
         torch.cuda.synchronize()
         got = bits_from_dev(y)
     return b, ws, got, (dp, db, run)
+
+
+def assert_same_up_to_rounding(a_bits, b_bits):
+    """Two bf16 results of the same sums formed in a different fp32 order: equal almost
+    everywhere, never more than one bf16 step apart."""
+    a = W.bf16_bits_to_f32(a_bits).astype(np.float64)
+    b = W.bf16_bits_to_f32(b_bits).astype(np.float64)
+    # the same sums in another fp32 order: one bf16 step where the value is of normal size; where
+    # terms cancel, what remains is the fp32 rounding of the row's largest values
+    row = np.maximum(np.abs(a).max(axis=1, keepdims=True), np.abs(b).max(axis=1, keepdims=True))
+    bound = bf16_ulp(np.maximum(np.abs(a), np.abs(b))) + 3e-5 * row
+    assert (np.abs(a - b) <= bound).all() and (a_bits != b_bits).mean() < 0.02
 
 
 SHAPES = [(8, 200, 328), (16, 200, 328), (32, 72, 136), (64, 264, 520), (16, 1024, 1024),
@@ -155,7 +167,11 @@ def test_apply_is_bit_identical_to_shrink_then_expand(rank, h_in, h_out, n, toke
     L.lora_apply(dp.pool, 0, 0, x, x.shape[1], None, db.seg, y, y.shape[1], run.v, dt)
     torch.cuda.synchronize()
     bits = torch.int32 if out_f32 else torch.int16
-    assert torch.equal(y.view(bits), y_ref.view(bits))
+    if L.lora_group_launches(dp.pool, 0, 1, tokens, db.seg, dt) == 2:
+        assert torch.equal(y.view(bits), y_ref.view(bits))
+    else:
+        # one launch: the K range is split differently, so sums differ in fp32 rounding only
+        assert_same_up_to_rounding(bits_from_dev(y), bits_from_dev(y_ref))
     if not out_f32:
         check_accumulate(bits_from_dev(y), oracle_projection(b, ws, 0, 0), "apply")
 
@@ -181,8 +197,13 @@ def test_group_of_three_projections_matches_single_calls(rank, tokens, n):
         ref[p.name] = y
     run.apply(0)
     torch.cuda.synchronize()
+    one_launch = L.lora_group_launches(dp.pool, 0, 3, tokens, db.seg) == 1
+    assert one_launch == (tokens == 70)            # the small batch runs as one launch
     for j, p in enumerate(projs):
-        assert torch.equal(db.y[p.name], ref[p.name]), p.name
+        if one_launch:
+            assert_same_up_to_rounding(bits_from_dev(db.y[p.name]), bits_from_dev(ref[p.name]))
+        else:
+            assert torch.equal(db.y[p.name], ref[p.name]), p.name
         check_accumulate(bits_from_dev(db.y[p.name]), oracle_projection(b, ws, 0, j), p.name)
 
 
