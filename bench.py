@@ -122,7 +122,7 @@ def make_phases(L, W, dp, db, run, acct, down_combine=False):
 
 
 def launches_per_step(w, dp, db, run):
-    """How many kernel launches one step takes: 1 for the segment build, then per group of
+    """How many kernel launches one step takes: 1 or 2 for the segment build, then per group of
     projections 1 if the library runs shrink and expand as one launch, else 2 (3 for batches of
     long segments, whose expand has a launch of its own for the operand images)."""
     import paper_2604_07173_amd as L
@@ -130,7 +130,8 @@ def launches_per_step(w, dp, db, run):
     if one is None:
         return None
     groups = [(0, 2), (2, 1)] if w.kind == "moe" else run.groups
-    return 1 + sum(L.lora_group_launches(dp.pool, j, c, db.P, db.seg) for j, c in groups)
+    return L.lora_segments_launches(dp.pool, db.P) + sum(L.lora_group_launches(dp.pool, j, c, db.P, db.seg)
+                                                          for j, c in groups)
 
 
 def measure(name, args, steps, warmup, with_cpu_baseline):

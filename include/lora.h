@@ -45,7 +45,11 @@ typedef enum lora_status {
 
 enum { LORA_DTYPE_BF16 = 0, LORA_DTYPE_F32 = 1 };
 enum { LORA_MOE_UPGATE = 0, LORA_MOE_DOWN = 1 };
-enum { LORA_MAX_PROJ = 8, LORA_MAX_ROWS = 1 << 14 };
+enum {
+    LORA_MAX_PROJ = 8,
+    LORA_MAX_ROWS = 1 << 14,        /* rows of a batch, any pool */
+    LORA_MAX_ROWS_LONG = 1 << 20    /* rows of a batch for pools of at most 256 (adapter, expert) keys */
+};
 
 /* bits of the device status word written by lora_build_segments */
 enum { LORA_STATUS_BAD_ADAPTER = 1u, LORA_STATUS_BAD_EXPERT = 2u };
@@ -215,10 +219,18 @@ size_t lora_segments_ws_bytes(int P);
 
 /*
  * adapter_id: device int32 [P], -1 = no adapter.  expert_id: device int32 [P] or NULL for a
- * dense layer.  P = 0 is a valid no-op that writes counts = 0.  P <= LORA_MAX_ROWS.
+ * dense layer.  P = 0 is a valid no-op that writes counts = 0.  P <= LORA_MAX_ROWS; pools with at
+ * most 256 keys (n_adapters * n_experts) take up to LORA_MAX_ROWS_LONG rows (batches of long
+ * segments, as in prefill); beyond that LORA_ERR_TOO_LARGE.
  * `seg`: the caller fills the six device pointers; the call fills P and tile_rows.
- * ws: device scratch of lora_segments_ws_bytes(P) (a small reserve: the builder sorts in LDS).
+ * ws: device scratch of lora_segments_ws_bytes(P) (short batches are sorted in LDS by one
+ * workgroup; long ones by several, which keep their per-chunk counts here).
  */
+/* Kernel launches lora_build_segments enqueues for a batch of P rows on this pool: 1 (one
+ * workgroup) or 2 (long batches of few keys, several workgroups); negative on a bad argument.
+ * A host-side query; it enqueues nothing. */
+int lora_segments_launches(const lora_pool *pool, int P);
+
 int lora_build_segments(const lora_pool *pool, const int32_t *adapter_id,
                         const int32_t *expert_id, int P, lora_segments *seg,
                         void *ws, size_t ws_bytes, void *stream);

@@ -14,6 +14,7 @@ LORA_DTYPE_BF16, LORA_DTYPE_F32 = 0, 1
 LORA_MOE_UPGATE, LORA_MOE_DOWN = 0, 1
 LORA_MAX_PROJ = 8
 LORA_MAX_ROWS = 1 << 14
+LORA_MAX_ROWS_LONG = 1 << 20
 LORA_STATIC_WS_BYTES = 16 << 20
 
 EXPORTED_SYMBOLS = [
@@ -21,7 +22,7 @@ EXPORTED_SYMBOLS = [
     "lora_pool_load_unit", "lora_pool_load_adapter_layer", "lora_pool_adapter_layer_bytes",
     "lora_pool_load_adapter_async", "lora_pool_set_adapter", "lora_pool_wait_layer", "lora_pool_layer_ready", "lora_pool_read_unit",
     "lora_pool_unit_layout", "lora_pool_device_table", "lora_pool_destroy",
-    "lora_segments_ws_bytes", "lora_build_segments", "lora_v_bytes", "lora_shrink",
+    "lora_segments_ws_bytes", "lora_segments_launches", "lora_build_segments", "lora_v_bytes", "lora_shrink",
     "lora_provision_iar", "lora_provision_min_cache", "lora_provision_memory_bytes",
     "lora_expand", "lora_apply", "lora_group_ws_bytes", "lora_group_launches", "lora_apply_group", "lora_moe_ws_bytes", "lora_moe_apply", "lora_moe_apply_static", "lora_moe_combine_ws_bytes", "lora_moe_down_combine", "lora_moe_shrink", "lora_moe_expand",
 ]
@@ -109,6 +110,8 @@ def load_library():
     lib.lora_pool_destroy.argtypes = [vp]
     lib.lora_segments_ws_bytes.restype = sz
     lib.lora_segments_ws_bytes.argtypes = [i32]
+    lib.lora_segments_launches.restype = i32
+    lib.lora_segments_launches.argtypes = [vp, i32]
     lib.lora_build_segments.restype = i32
     lib.lora_build_segments.argtypes = [vp, vp, vp, i32, C.POINTER(_Segments), vp, sz, vp]
     lib.lora_v_bytes.restype = sz
@@ -328,6 +331,10 @@ def lora_pool_destroy(pool):
 
 def lora_segments_ws_bytes(P: int) -> int:
     return int(load_library().lora_segments_ws_bytes(P))
+
+
+def lora_segments_launches(pool, P: int) -> int:
+    return int(load_library().lora_segments_launches(_h(pool), P))
 
 
 class Segments:

@@ -9,9 +9,9 @@ import sys
 PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "liblora.so")
-SOURCES = ["api.hip", "pack.hip", "segments.hip", "shrink.hip", "expand.hip",
+SOURCES = ["api.hip", "pack.hip", "segments.hip", "segments_large.hip", "shrink.hip", "expand.hip",
            "shrink_decode.hip", "expand_decode.hip", "fused_decode.hip", "combine.hip", "provision.cpp"]
-HEADERS = ["lora_internal.h", "lora_layout.h", "lora_device.h", "expand_common.h", "expand_item.h", "shrink_wave.h", os.path.join("..", "..", "include", "lora.h"),
+HEADERS = ["lora_internal.h", "lora_layout.h", "lora_device.h", "expand_common.h", "expand_item.h", "shrink_wave.h", "segments_common.h", os.path.join("..", "..", "include", "lora.h"),
            os.path.join("..", "..", "include", "lora_provision.h")]
 
 HIPCC_FLAGS = [

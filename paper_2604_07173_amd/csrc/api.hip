@@ -902,7 +902,22 @@ int lora_pool_destroy(lora_pool *pool)
 size_t lora_segments_ws_bytes(int P)
 {
     if (P < 0) return 0;
-    return 256;   // the builder sorts out of LDS; the global scratch is a reserve
+    // a single workgroup sorts out of LDS; the multi-workgroup builder of long batches keeps
+    // its per-chunk counts here
+    return std::max<size_t>(256, segments_large_ws_bytes(P));
+}
+
+int lora_segments_launches(const lora_pool *pool, int P)
+{
+    int rc = check_pool(pool);
+    if (rc != LORA_OK) return rc;
+    if (P < 0) return LORA_ERR_INVALID_ARG;
+    SegParams sp;
+    memset(&sp, 0, sizeof sp);
+    sp.P = P;
+    const uint32_t n_keys = (uint32_t)pool->d.n_adapters * (uint32_t)pool->d.n_experts;
+    sp.passes = n_keys <= 256 ? 1 : 2;         // only "one pass or more" matters here
+    return segments_large_handles(sp) ? 2 : 1;
 }
 
 int lora_build_segments(const lora_pool *pool, const int32_t *adapter_id, const int32_t *expert_id,
@@ -911,8 +926,12 @@ int lora_build_segments(const lora_pool *pool, const int32_t *adapter_id, const 
     int rc = check_pool(pool);
     if (rc != LORA_OK) return rc;
     if (!seg || P < 0) return LORA_ERR_INVALID_ARG;
-    if (P > LORA_MAX_ROWS) return LORA_ERR_TOO_LARGE;
     if (!seg->counts || !seg->status) return LORA_ERR_INVALID_ARG;
+    // batches beyond what one workgroup holds in LDS need the multi-workgroup builder, which
+    // takes key spaces of one 8-bit pass
+    if (P > LORA_MAX_ROWS &&
+        (P > LORA_MAX_ROWS_LONG || (int64_t)pool->d.n_adapters * pool->d.n_experts > 256))
+        return LORA_ERR_TOO_LARGE;
     if (P > 0) {
         if (!adapter_id || !seg->perm || !seg->seg_start || !seg->seg_key || !seg->tiles || !ws)
             return LORA_ERR_INVALID_ARG;
@@ -920,10 +939,6 @@ int lora_build_segments(const lora_pool *pool, const int32_t *adapter_id, const 
         if (!aligned(ws, 16) || !aligned(seg->tiles, 16)) return LORA_ERR_MISALIGNED;
         if (ws_bytes < lora_segments_ws_bytes(P)) return LORA_ERR_BUFFER_TOO_SMALL;
     }
-    seg->P = P;
-    seg->tile_rows = pick_tile_rows(pool, P);
-    seg->n_keys = pool->d.n_adapters * pool->d.n_experts;
-    seg->reserved = 0;
     SegParams sp;
     memset(&sp, 0, sizeof sp);
     sp.adapter_id = adapter_id;
@@ -931,7 +946,7 @@ int lora_build_segments(const lora_pool *pool, const int32_t *adapter_id, const 
     sp.P = P;
     sp.n_adapters = pool->d.n_adapters;
     sp.n_experts = pool->d.n_experts;
-    sp.tile_rows = seg->tile_rows;
+    sp.tile_rows = pick_tile_rows(pool, P);
     const uint32_t n_keys = (uint32_t)pool->d.n_adapters * (uint32_t)pool->d.n_experts;
     int bits = 1;
     while (((n_keys - 1) >> bits) != 0) ++bits;    // bits of the largest key
@@ -943,7 +958,11 @@ int lora_build_segments(const lora_pool *pool, const int32_t *adapter_id, const 
     sp.tiles = seg->tiles;
     sp.counts = seg->counts;
     sp.status = seg->status;
-    LORA_HIP(launch_segments(sp, static_cast<hipStream_t>(stream)));
+    seg->P = P;
+    seg->tile_rows = pick_tile_rows(pool, P);
+    seg->n_keys = pool->d.n_adapters * pool->d.n_experts;
+    seg->reserved = 0;
+    LORA_HIP(launch_segments(sp, ws, static_cast<hipStream_t>(stream)));
     return LORA_OK;
 }
 

@@ -73,13 +73,25 @@ struct SegParams {
     int tile_rows;
     int passes;              // radix passes of 8 bits over the key
     int key_bits;            // bits of the largest key
-    int bucket_shift;        // set by launch_segments: log2 of counter words per thread
     int32_t *perm;
     int32_t *seg_start;
     int32_t *seg_key;
     lora_tile *tiles;
     int32_t *counts;
     uint32_t *status;
+};
+
+// the multi-workgroup segment builder (segments_large.hip)
+struct LargeSegParams {
+    SegParams p;
+    unsigned *header;        // [0] = active rows, written by the first pass for the next
+    unsigned *wg_hist;       // [chunks][256] digit counts per chunk
+    unsigned *wg_info;       // [chunks][2] active rows and status bits per chunk
+    unsigned *key_g;         // [P] key of every row (kept for later passes), may be null
+    const unsigned *order_in;    // rows in the order the previous pass left them
+    unsigned *order_out;
+    int G;                   // chunks = workgroups
+    int pass;                // 8-bit digit this pass sorts by
 };
 
 struct ShrinkParams {
@@ -158,7 +170,10 @@ hipError_t launch_unpack_A(const PackParams &p, hipStream_t s);   // src = packe
 hipError_t launch_unpack_B(const PackParams &p, hipStream_t s);
 hipError_t launch_set_adapter(Unit *table, int n_layers, int n_adapters, int per_adapter, int adapter,
                               int rank, float scale, hipStream_t s);
-hipError_t launch_segments(const SegParams &p, hipStream_t s);
+hipError_t launch_segments(const SegParams &p, void *ws, hipStream_t s);
+hipError_t launch_segments_large(const SegParams &p, void *ws, hipStream_t s);
+size_t segments_large_ws_bytes(int P);
+bool segments_large_handles(const SegParams &p);    // does the multi-workgroup builder take this batch?
 hipError_t launch_shrink(const ShrinkParams &p, hipStream_t s);
 int shrink_long_tiles();                                 // tiles per work item of launch_shrink
 hipError_t launch_expand(const ExpandParams &p, hipStream_t s);

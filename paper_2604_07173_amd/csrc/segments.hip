@@ -26,15 +26,15 @@
 // * Counting path (segments_bucket_kernel; many short segments): described at the kernel.
 #include <cstdlib>
 
-#include "lora_internal.h"
+#include "segments_common.h"
 
 namespace lora {
 
 namespace {
 
-constexpr int kThreads = 1024;
-constexpr int kWaves = kThreads / 64;
-constexpr int kBins = 256;
+constexpr int kThreads = kSegThreads;
+constexpr int kWaves = kSegWaves;
+constexpr int kBins = kSegBins;
 constexpr int kMaxItems = LORA_MAX_ROWS / kThreads;   // positions per thread, fits a 32-bit mask
 static_assert(kMaxItems <= 32, "boundary flags are kept in a 32-bit mask");
 
@@ -44,70 +44,6 @@ struct ScanLds {
     int mn[kWaves];
     unsigned two[kWaves][2];
 };
-
-// inclusive prefix sum over the 64 lanes on the cross-lane data path (no LDS round trips):
-// shifts inside the rows of 16 lanes, then lane 15 of a row added to the next row (rows 1
-// and 3), then lane 31 added to rows 2 and 3.  A lane without a source adds 0.
-__device__ inline unsigned wave_incl_sum(unsigned x)
-{
-    x += (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x111, 0xf, 0xf, false);   // row_shr:1
-    x += (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x112, 0xf, 0xf, false);   // row_shr:2
-    x += (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x114, 0xf, 0xf, false);   // row_shr:4
-    x += (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x118, 0xf, 0xf, false);   // row_shr:8
-    x += (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x142, 0xa, 0xf, false);   // row_bcast:15
-    x += (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x143, 0xc, 0xf, false);   // row_bcast:31
-    return x;
-}
-
-// exclusive prefix sum over the workgroup, plus the total
-__device__ __noinline__ int block_excl_sum(int v, int *total, volatile int *wave_sums)
-{
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    const int inc = (int)wave_incl_sum((unsigned)v);
-    __syncthreads();
-    if (lane == 63) wave_sums[w] = inc;
-    __syncthreads();
-    // wave totals: lane k of the first 16 fetches total k, scalar reads of the lanes add them
-    const int mine = wave_sums[lane & (kWaves - 1)];
-    int tot = 0, base = 0;
-#pragma unroll
-    for (int k = 0; k < kWaves; ++k) {
-        const int t = __builtin_amdgcn_readlane(mine, k);
-        tot += t;
-        base += k < w ? t : 0;
-    }
-    *total = tot;
-    return base + inc - v;
-}
-
-// exclusive prefix sums of two values over the workgroup, plus their totals; one barrier
-__device__ inline void block_excl_sum2(unsigned a, unsigned b, volatile unsigned (*wave_sums)[2],
-                                       unsigned *a_before, unsigned *b_before, unsigned *a_total,
-                                       unsigned *b_total)
-{
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    const unsigned ia = wave_incl_sum(a), ib = wave_incl_sum(b);
-    if (lane == 63) {
-        wave_sums[w][0] = ia;
-        wave_sums[w][1] = ib;
-    }
-    __syncthreads();
-    const unsigned ma = wave_sums[lane & (kWaves - 1)][0], mb = wave_sums[lane & (kWaves - 1)][1];
-    unsigned ta = 0, tb = 0, ba = 0, bb = 0;
-#pragma unroll
-    for (int k = 0; k < kWaves; ++k) {
-        const unsigned xa = (unsigned)__builtin_amdgcn_readlane((int)ma, k);
-        const unsigned xb = (unsigned)__builtin_amdgcn_readlane((int)mb, k);
-        ta += xa;
-        tb += xb;
-        ba += k < w ? xa : 0u;
-        bb += k < w ? xb : 0u;
-    }
-    *a_before = ba + ia - a;
-    *b_before = bb + ib - b;
-    *a_total = ta;
-    *b_total = tb;
-}
 
 // three scans with one pair of barriers: exclusive sum of `cnt` (and total), exclusive
 // running max of `last` over earlier threads, exclusive running min of `first` over later
@@ -158,67 +94,30 @@ __device__ inline void block_scan3(int cnt, int last, int first, ScanLds *s,
     *first_after = lane < 63 ? min(mn, nmin) : mn;
 }
 
-// Lanes of the wave whose digit equals mine (restricted to valid lanes), as two 32-bit
-// halves.  Per digit bit that can be set: one ballot, then keep the lanes whose bit equals mine.
-struct Match {
-    unsigned lo, hi;
-};
-
-__device__ __noinline__ Match match_digit(unsigned digit, bool valid, int nbits)
-{
-    const unsigned long long v = __ballot(valid);
-    Match m = {(unsigned)v, (unsigned)(v >> 32)};
-#pragma unroll 1
-    for (int b = 0; b < nbits; ++b) {
-        const unsigned bit = (digit >> b) & 1u;
-        const unsigned long long bal = __ballot(valid && bit);
-        const unsigned same = 0u - bit;                  // all ones if my bit is set
-        m.lo &= ~((unsigned)bal ^ same);                 // bit ? bal : ~bal
-        m.hi &= ~((unsigned)(bal >> 32) ^ same);
-    }
-    return m;
-}
-
-// number of lanes below mine in the mask
-__device__ inline unsigned lanes_below(Match m)
-{
-    return __builtin_amdgcn_mbcnt_hi(m.hi, __builtin_amdgcn_mbcnt_lo(m.lo, 0u));
-}
-
-constexpr unsigned kNoKey = 0xFFFFFFFFu;               // row without adapter: left out of the order
-
-// key of a row from its ids, or kNoKey; ids that are neither valid nor -1 are reported in `bad`
-__device__ inline unsigned row_key(const SegParams &p, int a, int e, unsigned &bad)
-{
-    const bool a_ok = a >= 0 && a < p.n_adapters;
-    const bool e_ok = e >= 0 && e < p.n_experts;
-    const bool ok = a_ok && e_ok;
-    if (a != -1 && !ok)
-        bad |= (a_ok ? 0u : (unsigned)LORA_STATUS_BAD_ADAPTER) |
-               (e_ok ? 0u : (unsigned)LORA_STATUS_BAD_EXPERT);
-    return ok ? (unsigned)a * (unsigned)p.n_experts + (unsigned)e : kNoKey;
-}
-
-// key_of[i] for all rows; `each(i, key)` is called once per row.  The id loads of four rows
-// are issued before the first is used (the ids come from HBM; one round trip per row would
-// otherwise dominate large batches).
-template <class F>
+// key_of[i] for all rows; `each(i, key)` is called once per row.  The id loads of up to eight
+// rows are issued before the first is used (the ids come from HBM; one round trip per row
+// would otherwise dominate large batches).
+template <int NT = kThreads, class F>
 __device__ inline void all_row_keys(const SegParams &p, unsigned *key_of, unsigned &bad, F each)
 {
-    constexpr int U = 4;
+    constexpr int U = 8;
     const int tid = threadIdx.x;
 #pragma unroll 1
-    for (int i0 = tid; i0 < p.P; i0 += U * kThreads) {
+    for (int i0 = tid; i0 < p.P; i0 += U * NT) {
         int a[U], e[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int i = min(i0 + u * kThreads, p.P - 1);     // a valid row: the load is unconditional
-            a[u] = p.adapter_id[i];
-            e[u] = p.expert_id ? p.expert_id[i] : 0;
+            const int i = i0 + u * NT;
+            a[u] = -1;
+            e[u] = 0;
+            if (i < p.P) {
+                a[u] = p.adapter_id[i];
+                if (p.expert_id) e[u] = p.expert_id[i];
+            }
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int i = i0 + u * kThreads;
+            const int i = i0 + u * NT;
             if (i < p.P) {
                 const unsigned k = row_key(p, a[u], e[u], bad);
                 key_of[i] = k;
@@ -488,9 +387,18 @@ __global__ __launch_bounds__(kThreads) void segments_kernel(SegParams p)
 constexpr int kMaxBucket = 256;
 typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 
-__global__ __launch_bounds__(kThreads) void segments_bucket_kernel(SegParams p)
+// SHIFT = log2 of the counter words a thread owns (1 .. 32 words: up to 65536 keys); a
+// compile-time constant so that a thread's words live in registers between the scan and the
+// passes that need them again, and every loop over them is unrolled with its LDS reads in
+// flight together.
+template <int NT, int SHIFT>
+__global__ __launch_bounds__(NT) void segments_bucket_kernel(SegParams p)
 {
-    __shared__ unsigned wave_sums[kWaves][2];
+    constexpr int WPT = 1 << SHIFT;                   // counter words per thread
+    constexpr int n_cnt = (NT << SHIFT) + NT;         // counter words incl. the skew
+    constexpr int NW = NT / 64;
+    constexpr bool kFallback = NT == kThreads;        // the radix path is written for kThreads
+    __shared__ unsigned wave_sums[NW][2];
     __shared__ unsigned status_bits;
     __shared__ int n_active_total;
     __shared__ unsigned longest;
@@ -499,14 +407,11 @@ __global__ __launch_bounds__(kThreads) void segments_bucket_kernel(SegParams p)
     const int tid = threadIdx.x, lane = tid & 63;
     const int P = p.P;
     const int P_pad = (P + 63) & ~63;
-    const int shift = p.bucket_shift;                 // log2 of the counter words per thread
-    const int wpt = 1 << shift;
-    const int n_cnt = (kThreads << shift) + kThreads; // counter words incl. the skew
     unsigned *key_of = reinterpret_cast<unsigned *>(dyn_lds);           // [P_pad]
     unsigned *cnt = key_of + P_pad;                                     // [n_cnt]
     unsigned *tmp = cnt + n_cnt;                                        // [P_pad] row | key << 16
     unsigned *seglist = tmp;               // key | first tile << 16 per segment, before tmp is used
-    auto slot = [&](unsigned word) { return word + (shift ? word >> shift : 0u); };
+    auto slot = [&](unsigned word) { return word + (SHIFT ? word >> SHIFT : 0u); };
     auto half_of = [&](unsigned key) { return (cnt[slot(key >> 1)] >> ((key & 1u) * 16u)) & 0xFFFFu; };
 
     if (tid == 0) {
@@ -514,14 +419,15 @@ __global__ __launch_bounds__(kThreads) void segments_bucket_kernel(SegParams p)
         n_active_total = 0;
         longest = 0;
     }
-    for (int b = tid; b < n_cnt; b += kThreads) cnt[b] = 0;
+#pragma unroll
+    for (int j = 0; j < WPT + 1; ++j) cnt[tid + j * NT] = 0;
     __syncthreads();
 
     // ---- 1. keys and counts --------------------------------------------------------------
     {
         int n_active = 0;
         unsigned bad = 0;
-        all_row_keys(p, key_of, bad, [&](int, unsigned k) {
+        all_row_keys<NT>(p, key_of, bad, [&](int, unsigned k) {
             if (k != kNoKey) {
                 ++n_active;
                 atomicAdd(&cnt[slot(k >> 1)], 1u << ((k & 1u) * 16u));
@@ -537,51 +443,55 @@ __global__ __launch_bounds__(kThreads) void segments_bucket_kernel(SegParams p)
     // ---- 2. scan over the keys; segments and tiles ----------------------------------------
     const int TR = p.tile_rows;                       // a power of two
     const int tr_shift = 31 - __clz(TR);
-    const unsigned w0 = (unsigned)tid << shift;       // my counter words: w0 .. w0 + wpt - 1
+    const unsigned w0 = (unsigned)tid << SHIFT;       // my counter words: w0 .. w0 + WPT - 1
     unsigned rs_before, rs_total, t_before, t_total;  // rows | segments << 16, and tiles
-    unsigned long long occupied = 0;                  // my keys that have rows (wpt <= 32 words)
+    unsigned cw[WPT];                                 // my words (two 16-bit counts each)
     {
-        unsigned rows = 0, tiles = 0, mx = 0;
-#pragma unroll 1
-        for (int j = 0; j < wpt; ++j) {
-            const unsigned c = cnt[slot(w0 + j)];
-            const unsigned lo = c & 0xFFFFu, hi = c >> 16;
+        unsigned rows = 0, tiles = 0, mx = 0, segs = 0;
+#pragma unroll
+        for (int j = 0; j < WPT; ++j) cw[j] = cnt[slot(w0 + j)];
+#pragma unroll
+        for (int j = 0; j < WPT; ++j) {
+            const unsigned lo = cw[j] & 0xFFFFu, hi = cw[j] >> 16;
             rows += lo + hi;
             tiles += ((lo + TR - 1) >> tr_shift) + ((hi + TR - 1) >> tr_shift);
             mx = max(mx, max(lo, hi));
-            occupied |= (unsigned long long)((lo ? 1u : 0u) | (hi ? 2u : 0u)) << (2 * j);
+            segs += (lo ? 1u : 0u) + (hi ? 1u : 0u);
         }
-        if (mx > kMaxBucket) atomicMax(&longest, mx);
+        if (kFallback && mx > kMaxBucket) atomicMax(&longest, mx);
         // a batch has at most 16384 rows, so rows and segments share a word
-        block_excl_sum2(rows | ((unsigned)__popcll(occupied) << 16), tiles, wave_sums, &rs_before,
-                        &t_before, &rs_total, &t_total);
+        block_excl_sum2<NW>(rows | (segs << 16), tiles, wave_sums, &rs_before, &t_before, &rs_total,
+                        &t_total);
     }
-    if (longest > kMaxBucket) {        // same value in every thread: read after the scan's barrier
-        __syncthreads();
-        radix_body(p);
-        return;
+    if constexpr (kFallback) {
+        if (longest > kMaxBucket) {    // same value in every thread: read after the scan's barrier
+            __syncthreads();
+            radix_body(p);
+            return;
+        }
     }
     const int P_act = (int)(rs_total & 0xFFFFu);
     const int S = (int)(rs_total >> 16);
     const int n_tiles = (int)t_total;
     {
-        // list of the occupied keys with the first tile of each (a loop over my set bits
-        // only: most keys of a large key space are empty), then the start of every key in
-        // place of its count
+        // list of the occupied keys with the first tile of each, and the start of every key in
+        // place of its count (all from the words in registers: nothing is read back)
         int sidx = (int)(rs_before >> 16);
         unsigned tix = t_before;
-#pragma unroll 1
-        for (unsigned long long rest = occupied; rest; rest &= rest - 1) {
-            const int b = __ffsll((long long)rest) - 1;
-            const unsigned n = (cnt[slot(w0 + (b >> 1))] >> (16 * (b & 1))) & 0xFFFFu;
-            seglist[sidx++] = (w0 * 2 + b) | (tix << 16);
-            tix += (n + TR - 1) >> tr_shift;
-        }
         unsigned at = rs_before & 0xFFFFu;
-#pragma unroll 1
-        for (int j = 0; j < wpt; ++j) {
-            const unsigned c = cnt[slot(w0 + j)];
-            const unsigned lo = c & 0xFFFFu, hi = c >> 16;
+#pragma unroll
+        for (int j = 0; j < WPT; ++j) {
+            const unsigned lo = cw[j] & 0xFFFFu, hi = cw[j] >> 16;
+            if (cw[j]) {                               // most words of a large key space are empty
+                if (lo) {
+                    seglist[sidx++] = (w0 + j) * 2 | (tix << 16);
+                    tix += (lo + TR - 1) >> tr_shift;
+                }
+                if (hi) {
+                    seglist[sidx++] = ((w0 + j) * 2 + 1) | (tix << 16);
+                    tix += (hi + TR - 1) >> tr_shift;
+                }
+            }
             cnt[slot(w0 + j)] = at | ((at + lo) << 16);
             at += lo + hi;
         }
@@ -589,7 +499,7 @@ __global__ __launch_bounds__(kThreads) void segments_bucket_kernel(SegParams p)
     __syncthreads();
     // segment records and tiles, one segment per thread and turn
 #pragma unroll 1
-    for (int sidx = tid; sidx < S; sidx += kThreads) {
+    for (int sidx = tid; sidx < S; sidx += NT) {
         const unsigned me = seglist[sidx];
         const unsigned next = seglist[min(sidx + 1, S - 1)];
         const int key = (int)(me & 0xFFFFu);
@@ -611,14 +521,19 @@ __global__ __launch_bounds__(kThreads) void segments_bucket_kernel(SegParams p)
     __syncthreads();
 
     // ---- 3. a place in the key's range for every row --------------------------------------
+    // four rows per turn: their key reads, fetching adds and stores overlap
 #pragma unroll 1
-    for (int i = tid; i < P; i += kThreads) {
-        const unsigned k = key_of[i];
-        if (k != kNoKey) {
-            const unsigned sh = (k & 1u) * 16u;
-            const unsigned old = atomicAdd(&cnt[slot(k >> 1)], 1u << sh);
-            tmp[(old >> sh) & 0xFFFFu] = (unsigned)i | (k << 16);
-        }
+    for (int i0 = tid; i0 < P; i0 += 4 * NT) {
+        unsigned k[4], old[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) k[u] = i0 + u * NT < P ? key_of[i0 + u * NT] : kNoKey;
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (k[u] != kNoKey) old[u] = atomicAdd(&cnt[slot(k[u] >> 1)], 1u << ((k[u] & 1u) * 16u));
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (k[u] != kNoKey)
+                tmp[(old[u] >> ((k[u] & 1u) * 16u)) & 0xFFFFu] = (unsigned)(i0 + u * NT) | (k[u] << 16);
     }
     if (tid < 4 && P_act + tid < ((P_act + 3) & ~3)) tmp[P_act + tid] = 0xFFFFFFFFu;   // filler
     __syncthreads();
@@ -628,7 +543,7 @@ __global__ __launch_bounds__(kThreads) void segments_bucket_kernel(SegParams p)
     // The bucket is read in aligned groups of four words; words of other keys (and the
     // filler behind the last row) fall outside [key << 16, mine) and count as not smaller.
 #pragma unroll 1
-    for (int pos = tid; pos < P_act; pos += kThreads) {
+    for (int pos = tid; pos < P_act; pos += NT) {
         const unsigned mine = tmp[pos];
         const unsigned k = mine >> 16, row = mine & 0xFFFFu, base = mine & 0xFFFF0000u;
         const int e = (int)half_of(k);
@@ -677,12 +592,26 @@ static size_t bucket_lds_bytes(int P, unsigned n_keys)
     return need > segments_lds_bytes(P) ? need : segments_lds_bytes(P);
 }
 
-hipError_t launch_segments(const SegParams &p_in, hipStream_t s)
+constexpr size_t kBucketLdsMax = 140 * 1024;
+
+template <int NT, int SHIFT>
+static hipError_t launch_bucket(const SegParams &p, size_t dyn, hipStream_t s)
+{
+    static hipError_t attr = hipFuncSetAttribute(
+        reinterpret_cast<const void *>(segments_bucket_kernel<NT, SHIFT>),
+        hipFuncAttributeMaxDynamicSharedMemorySize, (int)kBucketLdsMax);
+    if (attr != hipSuccess) return attr;
+    hipLaunchKernelGGL((segments_bucket_kernel<NT, SHIFT>), dim3(1), dim3(NT), dyn, s, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_segments(const SegParams &p_in, void *ws, hipStream_t s)
 {
     SegParams p = p_in;
+    // long batches of few keys: several workgroups (segments_large.hip)
+    if (segments_large_handles(p)) return launch_segments_large(p, ws, s);
     // short segments on average and counters that fit LDS beside the radix path's static
     // arrays: bucket path
-    constexpr size_t kBucketLdsMax = 140 * 1024;
     const unsigned n_keys = (unsigned)p.n_adapters * (unsigned)p.n_experts;
     // LORA_SEGMENT_PATH=radix forces the radix path (both give the same result)
     static const bool force_radix = [] {
@@ -694,14 +623,16 @@ hipError_t launch_segments(const SegParams &p_in, hipStream_t s)
     const bool radix_is_cheap = p.passes == 1 && (int64_t)p.P >= 8 * (int64_t)n_keys;
     if (!force_radix && !radix_is_cheap && (int64_t)p.P < 64 * (int64_t)n_keys && n_keys <= 0x10000u &&
         bucket_lds_bytes(p.P, n_keys) <= kBucketLdsMax) {
-        p.bucket_shift = bucket_shift_of(n_keys);
         const size_t dyn = bucket_lds_bytes(p.P, n_keys);
-        static hipError_t attr = hipFuncSetAttribute(
-            reinterpret_cast<const void *>(segments_bucket_kernel),
-            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kBucketLdsMax);
-        if (attr != hipSuccess) return attr;
-        hipLaunchKernelGGL(segments_bucket_kernel, dim3(1), dim3(kThreads), dyn, s, p);
-        return hipGetLastError();
+        const int shift = bucket_shift_of(n_keys);
+        switch (shift) {
+        case 0: return launch_bucket<kThreads, 0>(p, dyn, s);
+        case 1: return launch_bucket<kThreads, 1>(p, dyn, s);
+        case 2: return launch_bucket<kThreads, 2>(p, dyn, s);
+        case 3: return launch_bucket<kThreads, 3>(p, dyn, s);
+        case 4: return launch_bucket<kThreads, 4>(p, dyn, s);
+        default: return launch_bucket<kThreads, 5>(p, dyn, s);
+        }
     }
     const size_t dyn = segments_lds_bytes(p.P);
     if (dyn > 48 * 1024) {

@@ -5,6 +5,7 @@ import numpy as np
 import pytest
 import torch
 
+import paper_2604_07173_amd as L
 import workloads as W
 from gpu_common import check_accumulate, check_delta, oracle_projection
 from oracle import lora_oracle as O
@@ -125,3 +126,27 @@ def test_mixtral_widths_at_rank_32_and_64(rank, y_mode):
         assert np.array_equal(got[none], b.y_in[p.name][none])
     del dp, db
     torch.cuda.empty_cache()
+
+
+def test_batch_longer_than_one_workgroup_sorts():
+    """24 requests x 1024 tokens = 24576 rows (more than the 16384 a single workgroup of the
+    segment builder holds), 6 adapters, rank 16, 1032 -> 776: segments by the multi-workgroup
+    builder, long-segment kernels; sampled rows and one whole request against the oracle."""
+    w = W.Workload("t", "dense", 6, 1, 1, 16, (W.Proj("p", 1032, 776, "x"),), 24 * 1024, "contiguous",
+                   n_requests=24)
+    b = W.make_batch(w, 5, y_mode="zero")
+    ws = W.make_weights(w, 5, bank_elems=1 << 21)
+    dp, db = DevicePool(ws, b.scale), DeviceBatch(b)
+    LayerRunner(dp, db).step(0)
+    torch.cuda.synchronize()
+    assert db.P > L.LORA_MAX_ROWS and db.seg.c.tile_rows == 32
+    o = O.segments(b.adapter_id, None, w.n_adapters, 1)
+    counts = db.seg.counts.cpu().numpy()
+    assert counts[0] == o.S == 6 and counts[1] == o.P_act == db.P
+    assert np.array_equal(db.seg.perm.cpu().numpy(), o.perm)
+    rows = np.sort(np.concatenate([np.random.default_rng(5).choice(db.P, size=256, replace=False),
+                                   np.arange(17 * 1024, 18 * 1024)]))
+    rows = np.unique(rows)
+    res = oracle_projection(b, ws, 0, 0, rows=rows)
+    got = np.ascontiguousarray(bits_from_dev(db.y["p"])[rows])
+    check_delta(W.bf16_bits_to_f32(got).astype(np.float64), res.delta, "24576-row batch")

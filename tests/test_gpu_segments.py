@@ -55,6 +55,10 @@ CASES = [
     (4, 1000, 7, 5, 0.1), (5, 1024, 32, 8, 0.0), (6, 1025, 32, 8, 0.5), (7, 4097, 3, 2, 0.0),
     (8, 8192, 256, 128, 0.0), (9, 16384, 8, 1, 0.0), (10, 5000, 300, 300, 0.2),
     (11, 777, 1, 1, 1.0), (12, 16384, 1000, 64, 0.01),
+    # long batches of few keys: several workgroups, two launches; beyond 16384 rows only those
+    (13, 4096, 8, 1, 0.0), (14, 4097, 16, 16, 0.1), (15, 6143, 1, 1, 0.0), (16, 16385, 8, 1, 0.0),
+    (17, 40000, 32, 8, 0.05), (18, 65536 + 37, 3, 5, 0.3), (19, 200000, 256, 1, 0.01),
+    (20, 20480, 2, 1, 1.0),
 ]
 
 
@@ -215,8 +219,27 @@ def test_workload_id_structures():
 
 
 def test_too_many_rows_is_a_host_error():
-    pool = make_pool(2, 1)
+    """Beyond LORA_MAX_ROWS only pools of at most 256 keys are taken, up to LORA_MAX_ROWS_LONG."""
     seg = L.Segments(8)
     with pytest.raises(L.LoraError) as e:
-        L.lora_build_segments(pool, seg.perm, None, L.LORA_MAX_ROWS + 1, seg)
+        L.lora_build_segments(make_pool(2, 1), seg.perm, None, L.LORA_MAX_ROWS_LONG + 1, seg)
     assert e.value.status == -8
+    with pytest.raises(L.LoraError) as e:
+        L.lora_build_segments(make_pool(257, 1), seg.perm, None, L.LORA_MAX_ROWS + 1, seg)
+    assert e.value.status == -8
+    assert L.lora_segments_ws_bytes(L.LORA_MAX_ROWS_LONG) >= 256 * 4 * (L.LORA_MAX_ROWS_LONG // 2048)
+
+
+def test_one_hot_key_in_a_long_batch():
+    """Almost all of 50000 rows on one of 200 keys, the rest spread: chunks whose waves see a
+    single digit next to chunks that see many."""
+    P, n = 50000, 200
+    rng = np.random.default_rng(77)
+    aid = rng.integers(0, n, size=P).astype(np.int32)
+    aid[rng.random(P) < 0.9] = 137
+    aid[rng.random(P) < 0.02] = -1
+    aid[::5000] = n + 3                     # ids outside the pool: reported and dropped
+    pool = make_pool(n, 1)
+    seg = run_segments(pool, aid, None)
+    compare(seg, aid, None, n, 1)
+    assert int(seg.status.cpu()[0]) == 1
