@@ -42,6 +42,11 @@ def parse_args():
                     help="MoE workloads: replace the down application (update added to every pair's "
                          "row) by lora_moe_down_combine (routing-weighted sum into token rows); "
                          "a variant for comparison, not the headline")
+    ap.add_argument("--tokens", type=int, default=0,
+                    help="run the workload's shapes with another number of tokens (0 = as defined)")
+    ap.add_argument("--steps-only", action="store_true",
+                    help="only the warm-up and the timed steps, launched on the stream, then a short "
+                         "JSON line: what a kernel trace or a counter run should see")
     ap.add_argument("--launch", choices=["graph", "stream"], default="graph",
                     help="how the timed steps are launched: one HIP graph holding all K steps "
                          "(as a serving engine captures a decode iteration), or plain stream launches")
@@ -143,6 +148,8 @@ def measure(name, args, steps, warmup, with_cpu_baseline):
     from harness import DeviceBatch, DevicePool, LayerRunner
 
     w = W.WORKLOADS[name]
+    if getattr(args, "tokens", 0):
+        w = W.scaled(w, tokens=args.tokens)
     n_layers = 1 if args.hot else (args.layers or DEFAULT_LAYERS.get(name, 4))
     b = W.make_batch(w, args.seed, y_mode="normal")
     ws = W.make_weights(w, args.seed, n_layers=n_layers)
@@ -178,6 +185,11 @@ def measure(name, args, steps, warmup, with_cpu_baseline):
     t1 = time.perf_counter()
     stream_ms_per_step = (t1 - t0) * 1e3 / steps
     ms_per_step = stream_ms_per_step
+    if getattr(args, "steps_only", False):
+        return dict(workload=name, tokens=w.tokens, rows=int(db.P), ms_per_step=ms_per_step,
+                    launches_per_step=launches, segments=acct["S"], active_rows=acct["P_act"],
+                    algorithmic_bytes=int(acct["total"]),
+                    phase_bytes={ph.name: int(ph.bytes) for ph in phases})
     replay_ms = []
     if args.launch == "graph":
         # the same K steps recorded once into a HIP graph and replayed: no allocation, no
@@ -506,6 +518,9 @@ def main():
         torch.cuda.synchronize()
         del src, dst
         torch.cuda.empty_cache()
+    if args.steps_only:
+        print(json.dumps(measure(args.workload, args, args.steps, args.warmup, False)))
+        return 0
     ceiling = copy_ceiling_gbs()
     main_res = measure(args.workload, args, args.steps, args.warmup, not args.no_cpu_baseline)
     out = {

@@ -26,15 +26,17 @@ namespace lora {
 
 namespace {
 
+constexpr int kFusedWaves = 4;      // waves of a workgroup (eight or sixteen measured no faster)
+
 template <int R>
-__global__ __launch_bounds__(256, 2) void fused16_kernel(FusedParams p,
+__global__ __launch_bounds__(64 * kFusedWaves) void fused16_kernel(FusedParams p,
                                                          const lora_tile *__restrict__ tiles,
                                                          const Unit *__restrict__ units,
                                                          const int32_t *__restrict__ counts)
 {
     using Wave = ShrinkWave<R, 1, false>;
     constexpr int NACC = Wave::NACC, KU = Wave::KU;
-    __shared__ f32x4 red[4][NACC][64];
+    __shared__ f32x4 red[kFusedWaves][NACC][64];
     __shared__ __attribute__((aligned(16))) float vsh[kDecodeTileRows * R];
 
     const ShrinkParams &sp = p.s;
@@ -49,7 +51,7 @@ __global__ __launch_bounds__(256, 2) void fused16_kernel(FusedParams p,
     const int per_tile = ep.slice0[ep.n_fused];                  // workgroup items of one tile
     const int n_items = n_tiles * per_tile;
     const int kblocks = (sp.h_in + KU - 1) / KU;
-    const int kb_per_wave = (((kblocks + 3) >> 2) + 3) & ~3;     // whole steps of the wave's loop
+    const int kb_per_wave = (((kblocks + kFusedWaves - 1) / kFusedWaves) + 3) & ~3;   // whole steps of the wave's loop
 
     for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
         const int tile_ix = item / per_tile;
@@ -74,23 +76,17 @@ __global__ __launch_bounds__(256, 2) void fused16_kernel(FusedParams p,
         __syncthreads();
         // the four waves' sums in a fixed order -> v[row][j] in LDS
         constexpr int NOUT = (R == 8 ? 1 : NACC) * 64;
-        for (int o = tid; o < NOUT; o += 256) {
+        for (int o = tid; o < NOUT; o += 64 * kFusedWaves) {
             const int l = o & 63;
             const int a = R == 8 ? 0 : o >> 6;
             const int row = l & 15;
             const int j = a * 16 + (l >> 4) * 4;
             if (j < R) {
-                f32x4 s;
-                if (R == 8) {
-                    s = red[0][0][l] + red[0][1][l + 32];
-                    s += red[1][0][l] + red[1][1][l + 32];
-                    s += red[2][0][l] + red[2][1][l + 32];
-                    s += red[3][0][l] + red[3][1][l + 32];
-                } else {
-                    s = red[0][a][l];
-                    s += red[1][a][l];
-                    s += red[2][a][l];
-                    s += red[3][a][l];
+                f32x4 s = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int k = 0; k < kFusedWaves; ++k) {
+                    if (R == 8) s += red[k][0][l] + red[k][1][l + 32];
+                    else s += red[k][a][l];
                 }
                 *reinterpret_cast<f32x4 *>(&vsh[row * R + j]) = s;
             }
@@ -101,7 +97,7 @@ __global__ __launch_bounds__(256, 2) void fused16_kernel(FusedParams p,
         {
             const int cps = ep.cps[pj];
             const int s0 = slice * cps, s1 = min(s0 + cps, ep.n_chunks[pj]);
-            const int per = ((((s1 - s0) + 3) >> 2) + 1) & ~1;
+            const int per = ((((s1 - s0) + kFusedWaves - 1) / kFusedWaves) + 1) & ~1;
             const int c0 = s0 + wave * per, c1 = min(c0 + per, s1);
             if (c0 < c1) expand_tile_chunks<R, false, false>(ep, t, unit, pj, c0, c1, w.lane, vsh);
         }
@@ -112,7 +108,7 @@ __global__ __launch_bounds__(256, 2) void fused16_kernel(FusedParams p,
 template <int R>
 hipError_t launch_r(const FusedParams &p, hipStream_t s)
 {
-    hipLaunchKernelGGL((fused16_kernel<R>), dim3(p.s.grid), dim3(256), 0, s, p, p.s.tiles, p.s.units,
+    hipLaunchKernelGGL((fused16_kernel<R>), dim3(p.s.grid), dim3(64 * kFusedWaves), 0, s, p, p.s.tiles, p.s.units,
                        p.s.counts);
     return hipGetLastError();
 }
