@@ -126,15 +126,19 @@ def make_phases(L, W, dp, db, run, acct, down_combine=False):
     return phases
 
 
-def launches_per_step(w, dp, db, run):
+def launches_per_step(w, dp, db, run, combine=False):
     """How many kernel launches one step takes: 1 or 2 for the segment build, then per group of
     projections 1 if the library runs shrink and expand as one launch, else 2 (3 for batches of
-    long segments, whose expand has a launch of its own for the operand images)."""
+    long segments, whose expand has a launch of its own for the operand images).  With the
+    routing-weighted combine the down call is shrink, expand into pair rows and the combine."""
     import paper_2604_07173_amd as L
     one = getattr(L, "lora_group_launches", None)
     if one is None:
         return None
     groups = [(0, 2), (2, 1)] if w.kind == "moe" else run.groups
+    if combine:
+        return (L.lora_segments_launches(dp.pool, db.P) + L.lora_group_launches(dp.pool, 0, 2, db.P, db.seg) + 3
+                + (2 if db.seg.c.tile_rows > 16 else 0))
     return L.lora_segments_launches(dp.pool, db.P) + sum(L.lora_group_launches(dp.pool, j, c, db.P, db.seg)
                                                           for j, c in groups)
 
@@ -177,7 +181,7 @@ def measure(name, args, steps, warmup, with_cpu_baseline):
     for it in range(warmup):
         step(it)
     torch.cuda.synchronize()
-    launches = launches_per_step(w, dp, db, run)      # the segments are built by now
+    launches = launches_per_step(w, dp, db, run, combine)      # the segments are built by now
     t0 = time.perf_counter()
     for it in range(steps):
         step(warmup + it)
