@@ -47,8 +47,8 @@ enum { LORA_DTYPE_BF16 = 0, LORA_DTYPE_F32 = 1 };
 enum { LORA_MOE_UPGATE = 0, LORA_MOE_DOWN = 1 };
 enum {
     LORA_MAX_PROJ = 8,
-    LORA_MAX_ROWS = 1 << 14,        /* rows of a batch, any pool */
-    LORA_MAX_ROWS_LONG = 1 << 20    /* rows of a batch for pools of at most 256 (adapter, expert) keys */
+    LORA_MAX_ROWS = 1 << 14,        /* rows of a batch that one workgroup sorts (small workspace) */
+    LORA_MAX_ROWS_LONG = 1 << 20    /* rows of a batch, any pool */
 };
 
 /* bits of the device status word written by lora_build_segments */
@@ -219,16 +219,18 @@ size_t lora_segments_ws_bytes(int P);
 
 /*
  * adapter_id: device int32 [P], -1 = no adapter.  expert_id: device int32 [P] or NULL for a
- * dense layer.  P = 0 is a valid no-op that writes counts = 0.  P <= LORA_MAX_ROWS; pools with at
- * most 256 keys (n_adapters * n_experts) take up to LORA_MAX_ROWS_LONG rows (batches of long
- * segments, as in prefill); beyond that LORA_ERR_TOO_LARGE.
- * `seg`: the caller fills the six device pointers; the call fills P and tile_rows.
- * ws: device scratch of lora_segments_ws_bytes(P) (short batches are sorted in LDS by one
- * workgroup; long ones by several, which keep their per-chunk counts here).
+ * dense layer.  P = 0 is a valid no-op that writes counts = 0.  P <= LORA_MAX_ROWS_LONG, beyond
+ * that LORA_ERR_TOO_LARGE.
+ * `seg`: the caller fills the six device pointers; the call fills P, tile_rows and n_keys.
+ * ws: device scratch of lora_segments_ws_bytes(P).  Batches of up to LORA_MAX_ROWS rows are
+ * sorted in LDS by one workgroup; longer ones, and long ones of at most 256 keys
+ * (n_adapters * n_experts), by several workgroups, which keep per-chunk counts and (beyond
+ * LORA_MAX_ROWS rows) the rows' keys and two intermediate orders there: 12 bytes per row.
  */
 /* Kernel launches lora_build_segments enqueues for a batch of P rows on this pool: 1 (one
- * workgroup) or 2 (long batches of few keys, several workgroups); negative on a bad argument.
- * A host-side query; it enqueues nothing. */
+ * workgroup), 2 (several workgroups, at most 256 keys) or 2 per 8 key bits + 2 (several
+ * workgroups, larger key spaces); negative on a bad argument.  A host-side query; it enqueues
+ * nothing. */
 int lora_segments_launches(const lora_pool *pool, int P);
 
 int lora_build_segments(const lora_pool *pool, const int32_t *adapter_id,

@@ -907,6 +907,14 @@ size_t lora_segments_ws_bytes(int P)
     return std::max<size_t>(256, segments_large_ws_bytes(P));
 }
 
+static int key_bits_of(const lora_pool *pool)
+{
+    const uint32_t n_keys = (uint32_t)pool->d.n_adapters * (uint32_t)pool->d.n_experts;
+    int bits = 1;
+    while (((n_keys - 1) >> bits) != 0) ++bits;    // bits of the largest key
+    return bits;
+}
+
 int lora_segments_launches(const lora_pool *pool, int P)
 {
     int rc = check_pool(pool);
@@ -915,9 +923,9 @@ int lora_segments_launches(const lora_pool *pool, int P)
     SegParams sp;
     memset(&sp, 0, sizeof sp);
     sp.P = P;
-    const uint32_t n_keys = (uint32_t)pool->d.n_adapters * (uint32_t)pool->d.n_experts;
-    sp.passes = n_keys <= 256 ? 1 : 2;         // only "one pass or more" matters here
-    return segments_large_handles(sp) ? 2 : 1;
+    sp.key_bits = key_bits_of(pool);
+    sp.passes = (sp.key_bits + 7) / 8;
+    return segments_large_handles(sp) ? segments_large_launches(sp) : 1;
 }
 
 int lora_build_segments(const lora_pool *pool, const int32_t *adapter_id, const int32_t *expert_id,
@@ -927,11 +935,7 @@ int lora_build_segments(const lora_pool *pool, const int32_t *adapter_id, const 
     if (rc != LORA_OK) return rc;
     if (!seg || P < 0) return LORA_ERR_INVALID_ARG;
     if (!seg->counts || !seg->status) return LORA_ERR_INVALID_ARG;
-    // batches beyond what one workgroup holds in LDS need the multi-workgroup builder, which
-    // takes key spaces of one 8-bit pass
-    if (P > LORA_MAX_ROWS &&
-        (P > LORA_MAX_ROWS_LONG || (int64_t)pool->d.n_adapters * pool->d.n_experts > 256))
-        return LORA_ERR_TOO_LARGE;
+    if (P > LORA_MAX_ROWS_LONG) return LORA_ERR_TOO_LARGE;
     if (P > 0) {
         if (!adapter_id || !seg->perm || !seg->seg_start || !seg->seg_key || !seg->tiles || !ws)
             return LORA_ERR_INVALID_ARG;
@@ -947,11 +951,8 @@ int lora_build_segments(const lora_pool *pool, const int32_t *adapter_id, const 
     sp.n_adapters = pool->d.n_adapters;
     sp.n_experts = pool->d.n_experts;
     sp.tile_rows = pick_tile_rows(pool, P);
-    const uint32_t n_keys = (uint32_t)pool->d.n_adapters * (uint32_t)pool->d.n_experts;
-    int bits = 1;
-    while (((n_keys - 1) >> bits) != 0) ++bits;    // bits of the largest key
-    sp.key_bits = bits;
-    sp.passes = (bits + 7) / 8;
+    sp.key_bits = key_bits_of(pool);
+    sp.passes = (sp.key_bits + 7) / 8;
     sp.perm = seg->perm;
     sp.seg_start = seg->seg_start;
     sp.seg_key = seg->seg_key;

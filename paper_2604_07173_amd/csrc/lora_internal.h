@@ -90,6 +90,7 @@ struct LargeSegParams {
     unsigned *key_g;         // [P] key of every row (kept for later passes), may be null
     const unsigned *order_in;    // rows in the order the previous pass left them
     unsigned *order_out;
+    unsigned *chunk_info;    // [chunks][4] segment heads of every chunk of the sorted order
     int G;                   // chunks = workgroups
     int pass;                // 8-bit digit this pass sorts by
 };
@@ -174,6 +175,7 @@ hipError_t launch_segments(const SegParams &p, void *ws, hipStream_t s);
 hipError_t launch_segments_large(const SegParams &p, void *ws, hipStream_t s);
 size_t segments_large_ws_bytes(int P);
 bool segments_large_handles(const SegParams &p);    // does the multi-workgroup builder take this batch?
+int segments_large_launches(const SegParams &p);    // kernels it enqueues for it
 hipError_t launch_shrink(const ShrinkParams &p, hipStream_t s);
 int shrink_long_tiles();                                 // tiles per work item of launch_shrink
 hipError_t launch_expand(const ExpandParams &p, hipStream_t s);

@@ -19,9 +19,15 @@
 //            rows to their positions.
 // Up to 256 keys take one pass, and the scanned totals then are the segment table: every
 // workgroup knows it, workgroup 0 writes the segment records and the counts, and the tiles are
-// dealt out over all workgroups.  Up to 65536 keys take two passes (the second reads the rows in
-// the order the first left them) and a last launch that finds the segment boundaries in the
-// sorted keys.
+// dealt out over all workgroups.  Larger key spaces take one pass per 8 key bits (a pass reads
+// the rows in the order the previous one left them) and then two launches that find the segment
+// boundaries in the sorted keys:
+//   heads:  every workgroup marks the positions of its chunk whose key differs from the one
+//           before (segment heads) and writes how many there are, the first and the last, and
+//           how many tiles start at or behind the chunk's first head
+//   bounds: every workgroup scans those chunk records (segments and tiles of earlier chunks,
+//           the last head before the chunk, the first head behind it) and writes the segment
+//           records and tiles of its chunk.
 #include <string.h>
 
 #include "segments_common.h"
@@ -251,19 +257,231 @@ __global__ __launch_bounds__(kSegThreads) void seg_large_scatter_kernel(LargeSeg
     }
 }
 
+// ---- several passes: segment boundaries from the sorted keys ----------------------------------
+
+constexpr unsigned kNone = 0xFFFFFFFFu;
+constexpr int kPosPerThread = kChunk / kSegThreads;  // consecutive positions of a thread
+static_assert(kPosPerThread == 2, "the head scan below is written for two positions per thread");
+
+struct Heads {                                      // a thread's two consecutive sorted positions
+    unsigned pos0;
+    unsigned key[2];
+    bool in[2], head[2];
+    unsigned ord[2];                                // heads of the chunk up to and including the position
+};
+
+// Marks the segment heads of this workgroup's chunk of the sorted order, numbers them and lists
+// their positions in head_pos[].  n = rows in the order.
+__device__ inline void chunk_heads(const LargeSegParams &q, unsigned n, Heads &h, unsigned *head_pos,
+                                   int *scan_sums, int *n_heads)
+{
+    const int tid = threadIdx.x;
+    h.pos0 = (unsigned)blockIdx.x * kChunk + 2u * tid;
+    h.in[0] = h.pos0 < n;
+    h.in[1] = h.pos0 + 1 < n;
+    const int32_t *perm = q.p.perm;
+    const bool has_prev = h.in[0] && h.pos0 > 0;
+    const int32_t rp = has_prev ? perm[h.pos0 - 1] : 0;
+    const int32_t r0 = h.in[0] ? perm[h.pos0] : 0;
+    const int32_t r1 = h.in[1] ? perm[h.pos0 + 1] : 0;
+    const unsigned kp = has_prev ? q.key_g[rp] : kNoKey;
+    h.key[0] = h.in[0] ? q.key_g[r0] : kNoKey;
+    h.key[1] = h.in[1] ? q.key_g[r1] : kNoKey;
+    h.head[0] = h.in[0] && (!has_prev || h.key[0] != kp);
+    h.head[1] = h.in[1] && h.key[1] != h.key[0];
+    const int mine = (h.head[0] ? 1 : 0) + (h.head[1] ? 1 : 0);
+    const int before = block_excl_sum(mine, n_heads, scan_sums);            // barriers inside
+    h.ord[0] = (unsigned)before + (h.head[0] ? 1u : 0u);
+    h.ord[1] = h.ord[0] + (h.head[1] ? 1u : 0u);
+    if (h.head[0]) head_pos[h.ord[0] - 1] = h.pos0;
+    if (h.head[1]) head_pos[h.ord[1] - 1] = h.pos0 + 1;
+    __syncthreads();
+}
+
+// chunk record: {heads, first head, last head, tiles that start at or behind the first head}
+__global__ __launch_bounds__(kSegThreads) void seg_large_heads_kernel(LargeSegParams q)
+{
+    __shared__ unsigned head_pos[kChunk];
+    __shared__ int scan_sums[kSegWaves];
+    const unsigned n = q.header[0];
+    const unsigned tr_mask = (unsigned)q.p.tile_rows - 1u;                  // a power of two
+    Heads h;
+    int n_heads;
+    chunk_heads(q, n, h, head_pos, scan_sums, &n_heads);
+    int tiles = 0;
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+        if (h.in[j] && h.ord[j] >= 1 && ((h.pos0 + j - head_pos[h.ord[j] - 1]) & tr_mask) == 0) ++tiles;
+    int n_tiles;
+    block_excl_sum(tiles, &n_tiles, scan_sums);
+    if (threadIdx.x == 0) {
+        unsigned *rec = q.chunk_info + 4 * (size_t)blockIdx.x;
+        rec[0] = (unsigned)n_heads;
+        rec[1] = n_heads ? head_pos[0] : kNone;
+        rec[2] = n_heads ? head_pos[n_heads - 1] : kNone;
+        rec[3] = (unsigned)n_tiles;
+    }
+}
+
+// inclusive prefix maximum over the workgroup
+__device__ inline unsigned block_incl_max(unsigned v, volatile unsigned *wave_max)
+{
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const unsigned up = (unsigned)__shfl_up((int)v, o, 64);
+        if (lane >= o) v = max(v, up);
+    }
+    __syncthreads();
+    if (lane == 63) wave_max[w] = v;
+    __syncthreads();
+    unsigned base = 0;
+    for (int k = 0; k < w; ++k) base = max(base, wave_max[k]);
+    return max(v, base);
+}
+
+__global__ __launch_bounds__(kSegThreads) void seg_large_bounds_kernel(LargeSegParams q)
+{
+    __shared__ unsigned head_pos[kChunk];
+    __shared__ int scan_sums[kSegWaves];
+    __shared__ unsigned scan_two[kSegWaves][2];
+    __shared__ unsigned wave_max[kSegWaves];
+    __shared__ unsigned mine_of[6];     // this chunk: segments before, tiles before, last head before, first head behind; S, tiles
+    const SegParams &p = q.p;
+    const int tid = threadIdx.x;
+    const unsigned n = q.header[0];
+    const int TR = p.tile_rows;
+    const int tr_shift = 31 - __clz(TR);
+    const unsigned tr_mask = (unsigned)TR - 1u;
+
+    // ---- the chunk records: thread c looks at chunk c and, for the scan from the right, at
+    // chunk G-1-c (at most kSegThreads chunks: LORA_MAX_ROWS_LONG / kChunk)
+    const bool have = tid < q.G;
+    const unsigned *rec = q.chunk_info + 4 * (size_t)(have ? tid : 0);
+    const unsigned heads_c = have ? rec[0] : 0u, first_c = have ? rec[1] : kNone, last_c = have ? rec[2] : kNone,
+                   tiles_c = have ? rec[3] : 0u;
+    const unsigned first_r = have ? q.chunk_info[4 * (size_t)(q.G - 1 - tid) + 1] : kNone;
+    // last head in chunks before c: positions + 1, so that 0 means none
+    const unsigned incl_last = block_incl_max(last_c == kNone ? 0u : last_c + 1u, wave_max);
+    const unsigned up_last = (unsigned)__shfl_up((int)incl_last, 1, 64);
+    __syncthreads();
+    if ((tid & 63) == 63) wave_max[tid >> 6] = incl_last;
+    __syncthreads();
+    const unsigned carry1 = (tid & 63) ? up_last : (tid ? wave_max[(tid >> 6) - 1] : 0u);   // exclusive
+    // tiles of chunk c = those behind its first head + those between its start and that head,
+    // which continue the segment of the last head before the chunk
+    unsigned pre = 0;
+    if (have && carry1) {
+        const unsigned lo = (unsigned)tid * kChunk;
+        const unsigned hi = min(min(first_c, lo + (unsigned)kChunk), n);
+        if (hi > lo) {
+            const unsigned a = lo - (carry1 - 1u), b = hi - (carry1 - 1u);
+            pre = ((b + tr_mask) >> tr_shift) - ((a + tr_mask) >> tr_shift);
+        }
+    }
+    unsigned seg_before, tile_before, S, n_tiles;
+    __syncthreads();
+    block_excl_sum2(heads_c, tiles_c + pre, scan_two, &seg_before, &tile_before, &S, &n_tiles);
+    // first head in chunks behind chunk G-1-tid, as n - position so that a maximum finds it
+    const unsigned incl_first = block_incl_max(first_r == kNone ? 0u : n - first_r, wave_max);
+    const unsigned up_first = (unsigned)__shfl_up((int)incl_first, 1, 64);
+    __syncthreads();
+    if ((tid & 63) == 63) wave_max[tid >> 6] = incl_first;
+    __syncthreads();
+    const unsigned behind = (tid & 63) ? up_first : (tid ? wave_max[(tid >> 6) - 1] : 0u);   // exclusive
+    if (tid == (int)blockIdx.x) {
+        mine_of[0] = seg_before;
+        mine_of[1] = tile_before;
+        mine_of[2] = carry1;
+    }
+    if (have && q.G - 1 - tid == (int)blockIdx.x) mine_of[3] = n - behind;  // n if no head follows
+    if (tid == 0) {
+        mine_of[4] = S;
+        mine_of[5] = n_tiles;
+    }
+    __syncthreads();
+    const unsigned my_seg0 = mine_of[0], my_tile0 = mine_of[1], my_carry1 = mine_of[2], my_next = mine_of[3];
+
+    // ---- this chunk's segment records and tiles --------------------------------------------------
+    Heads h;
+    int n_heads;
+    chunk_heads(q, n, h, head_pos, scan_sums, &n_heads);
+    bool th[2];
+    unsigned start[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        start[j] = h.ord[j] >= 1 ? head_pos[h.ord[j] - 1] : my_carry1 - 1u;   // a position without a head before it has a carry
+        th[j] = h.in[j] && ((h.pos0 + j - start[j]) & tr_mask) == 0;
+    }
+    int tiles_total;
+    const int tiles_before = block_excl_sum((th[0] ? 1 : 0) + (th[1] ? 1 : 0), &tiles_total, scan_sums);
+    unsigned ti = my_tile0 + (unsigned)tiles_before;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const unsigned pos = h.pos0 + j;
+        const unsigned seg = my_seg0 + h.ord[j] - 1u;
+        if (h.head[j] && seg < (unsigned)p.P) {              // never beyond the caller's arrays
+            p.seg_start[seg] = (int32_t)pos;
+            p.seg_key[seg] = (int32_t)h.key[j];
+        }
+        if (th[j] && ti < (unsigned)p.P) {
+            const unsigned end = (int)h.ord[j] < n_heads ? head_pos[h.ord[j]] : my_next;
+            lora_tile t;
+            t.key = (int32_t)h.key[j];
+            t.row0 = (int32_t)pos;
+            t.n_rows = (int32_t)min((unsigned)TR, end - pos);
+            t.seg = (int32_t)seg;
+            p.tiles[ti] = t;
+        }
+        ti += th[j] ? 1u : 0u;
+    }
+    if (blockIdx.x == 0 && tid == 0) {
+        unsigned status = 0;
+        for (int c = 0; c < q.G; ++c) status |= q.wg_info[2 * c + 1];
+        p.seg_start[mine_of[4]] = (int32_t)n;
+        p.counts[0] = (int32_t)mine_of[4];
+        p.counts[1] = (int32_t)n;
+        p.counts[2] = (int32_t)mine_of[5];
+        p.counts[3] = 0;
+        p.status[0] = status;
+    }
+}
+
 }  // namespace
 
 static int segments_large_chunks(int P) { return (P + kChunk - 1) / kChunk; }
-
 // One pass (at most 256 keys) and a batch long enough for two launches of many workgroups to
-// beat one launch of a single workgroup.
-bool segments_large_handles(const SegParams &p) { return p.passes == 1 && p.P >= kLargeMinRows; }
+// beat one launch of a single workgroup; or a batch beyond what a single workgroup holds.
+bool segments_large_handles(const SegParams &p)
+{
+    return (p.passes == 1 && p.P >= kLargeMinRows) || p.P > LORA_MAX_ROWS;
+}
 
-size_t segments_large_ws_bytes(int P)
+int segments_large_launches(const SegParams &p) { return p.passes == 1 ? 2 : 2 * p.passes + 2; }
+
+namespace {
+struct LargeLayout {
+    size_t hist, info, chunk_info, key, order[2], total;
+};
+LargeLayout large_layout(int P)
 {
     const size_t G = (size_t)segments_large_chunks(P);
-    return 256 + align_up(G * kSegBins * sizeof(unsigned), 256) + align_up(G * 2 * sizeof(unsigned), 256);
+    LargeLayout L;
+    size_t o = 256;                                   // header
+    L.hist = o, o += align_up(G * kSegBins * sizeof(unsigned), 256);
+    L.info = o, o += align_up(G * 2 * sizeof(unsigned), 256);
+    L.chunk_info = o, o += align_up(G * 4 * sizeof(unsigned), 256);
+    // keys and two row orders: only batches beyond a single workgroup can need several passes here
+    const size_t rows = P > LORA_MAX_ROWS ? align_up((size_t)P * sizeof(unsigned), 256) : 0;
+    L.key = o, o += rows;
+    L.order[0] = o, o += rows;
+    L.order[1] = o, o += rows;
+    L.total = o;
+    return L;
 }
+}  // namespace
+
+size_t segments_large_ws_bytes(int P) { return large_layout(P).total; }
 
 hipError_t launch_segments_large(const SegParams &p, void *ws, hipStream_t s)
 {
@@ -271,16 +489,46 @@ hipError_t launch_segments_large(const SegParams &p, void *ws, hipStream_t s)
     memset(&q, 0, sizeof q);
     q.p = p;
     q.G = segments_large_chunks(p.P);
+    if (q.G > kSegThreads) return hipErrorInvalidValue;        // the bounds kernel holds a chunk record per thread
+    const LargeLayout L = large_layout(p.P);
     char *base = static_cast<char *>(ws);
     q.header = reinterpret_cast<unsigned *>(base);
-    q.wg_hist = reinterpret_cast<unsigned *>(base + 256);
-    q.wg_info = reinterpret_cast<unsigned *>(base + 256 + align_up((size_t)q.G * kSegBins * sizeof(unsigned), 256));
-    if (p.passes != 1) return hipErrorInvalidValue;
-    q.pass = 0;
-    hipLaunchKernelGGL((seg_large_count_kernel<true>), dim3(q.G), dim3(kSegThreads), 0, s, q);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((seg_large_scatter_kernel<true, true>), dim3(q.G), dim3(kSegThreads), 0, s, q);
+    q.wg_hist = reinterpret_cast<unsigned *>(base + L.hist);
+    q.wg_info = reinterpret_cast<unsigned *>(base + L.info);
+    q.chunk_info = reinterpret_cast<unsigned *>(base + L.chunk_info);
+    const dim3 grid(q.G), block(kSegThreads);
+    hipError_t e;
+    if (p.passes == 1) {
+        q.pass = 0;
+        hipLaunchKernelGGL((seg_large_count_kernel<true>), grid, block, 0, s, q);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+        hipLaunchKernelGGL((seg_large_scatter_kernel<true, true>), grid, block, 0, s, q);
+        return hipGetLastError();
+    }
+    if (p.P <= LORA_MAX_ROWS) return hipErrorInvalidValue;     // no room for keys and orders was asked for
+    q.key_g = reinterpret_cast<unsigned *>(base + L.key);
+    for (int pass = 0; pass < p.passes; ++pass) {
+        const bool last = pass == p.passes - 1;
+        q.pass = pass;
+        q.order_in = pass ? reinterpret_cast<const unsigned *>(base + L.order[(pass - 1) & 1]) : nullptr;
+        q.order_out = last ? nullptr : reinterpret_cast<unsigned *>(base + L.order[pass & 1]);
+        if (pass == 0) {
+            hipLaunchKernelGGL((seg_large_count_kernel<true>), grid, block, 0, s, q);
+            if ((e = hipGetLastError()) != hipSuccess) return e;
+            hipLaunchKernelGGL((seg_large_scatter_kernel<true, false>), grid, block, 0, s, q);
+        } else {
+            hipLaunchKernelGGL((seg_large_count_kernel<false>), grid, block, 0, s, q);
+            if ((e = hipGetLastError()) != hipSuccess) return e;
+            if (last)
+                hipLaunchKernelGGL((seg_large_scatter_kernel<false, true>), grid, block, 0, s, q);
+            else
+                hipLaunchKernelGGL((seg_large_scatter_kernel<false, false>), grid, block, 0, s, q);
+        }
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(seg_large_heads_kernel, grid, block, 0, s, q);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    hipLaunchKernelGGL(seg_large_bounds_kernel, grid, block, 0, s, q);
     return hipGetLastError();
 }
 

@@ -14,8 +14,8 @@ from harness import DeviceBatch, DevicePool, LayerRunner, bits_from_dev
 pytestmark = pytest.mark.gpu
 
 
-def run_config(name, seed, y_mode, sample=None, n_layers=1, layer=0):
-    w = W.WORKLOADS[name]
+def run_config(name, seed, y_mode, sample=None, n_layers=1, layer=0, w=None):
+    w = w or W.WORKLOADS[name]
     b = W.make_batch(w, seed, y_mode=y_mode)
     ws = W.make_weights(w, seed, n_layers=n_layers)
     print(f"[{name}] seed={seed} y={y_mode} P={w.pairs} pool...", flush=True)
@@ -65,6 +65,15 @@ def test_mixtral_moe_decode(y_mode):
 @pytest.mark.parametrize("y_mode", ["zero", "normal"])
 def test_finegrained_moe_decode(y_mode):
     run_config("finegrained_moe_decode", 1234, y_mode)
+
+
+def test_finegrained_moe_batch_beyond_one_workgroup_of_the_segment_builder():
+    """The fine-grained MoE shapes with 2304 tokens x top-8 = 18432 rows over 32768 (adapter,
+    expert) keys: more rows than one workgroup of the segment builder sorts and more keys than one
+    8-bit pass covers; segments bit-exact, sampled rows of every projection against the oracle."""
+    w = W.scaled(W.WORKLOADS["finegrained_moe_decode"], tokens=2304)
+    assert w.pairs > L.LORA_MAX_ROWS
+    run_config("finegrained_moe_18432_rows", 7, "zero", sample=512, w=w)
 
 
 def test_prefill_sampled_rows():

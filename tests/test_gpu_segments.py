@@ -55,10 +55,15 @@ CASES = [
     (4, 1000, 7, 5, 0.1), (5, 1024, 32, 8, 0.0), (6, 1025, 32, 8, 0.5), (7, 4097, 3, 2, 0.0),
     (8, 8192, 256, 128, 0.0), (9, 16384, 8, 1, 0.0), (10, 5000, 300, 300, 0.2),
     (11, 777, 1, 1, 1.0), (12, 16384, 1000, 64, 0.01),
-    # long batches of few keys: several workgroups, two launches; beyond 16384 rows only those
+    # long batches of few keys: several workgroups, two launches
     (13, 4096, 8, 1, 0.0), (14, 4097, 16, 16, 0.1), (15, 6143, 1, 1, 0.0), (16, 16385, 8, 1, 0.0),
     (17, 40000, 32, 8, 0.05), (18, 65536 + 37, 3, 5, 0.3), (19, 200000, 256, 1, 0.01),
     (20, 20480, 2, 1, 1.0),
+    # beyond 16384 rows with more than 256 keys: several workgroups, one pass per 8 key bits, then
+    # the segment boundaries from the sorted keys (two and three passes)
+    (21, 16385, 257, 1, 0.0), (22, 32768, 256, 128, 0.0), (23, 40000, 300, 7, 0.1),
+    (24, 100000, 70000, 1, 0.02), (25, 65536 + 2049, 3, 30000, 0.0), (26, 30000, 600, 500, 0.0),
+    (27, 20000, 300, 300, 1.0), (28, 262144 + 5, 512, 128, 0.01),
 ]
 
 
@@ -219,15 +224,44 @@ def test_workload_id_structures():
 
 
 def test_too_many_rows_is_a_host_error():
-    """Beyond LORA_MAX_ROWS only pools of at most 256 keys are taken, up to LORA_MAX_ROWS_LONG."""
+    """Batches of up to LORA_MAX_ROWS_LONG rows are taken, whatever the pool; beyond that the call
+    refuses before it looks at any buffer."""
     seg = L.Segments(8)
-    with pytest.raises(L.LoraError) as e:
-        L.lora_build_segments(make_pool(2, 1), seg.perm, None, L.LORA_MAX_ROWS_LONG + 1, seg)
-    assert e.value.status == -8
+    for pool in (make_pool(2, 1), make_pool(257, 1)):
+        with pytest.raises(L.LoraError) as e:
+            L.lora_build_segments(pool, seg.perm, None, L.LORA_MAX_ROWS_LONG + 1, seg)
+        assert e.value.status == -8
+    # a workspace sized for fewer rows is refused too
     with pytest.raises(L.LoraError) as e:
         L.lora_build_segments(make_pool(257, 1), seg.perm, None, L.LORA_MAX_ROWS + 1, seg)
-    assert e.value.status == -8
-    assert L.lora_segments_ws_bytes(L.LORA_MAX_ROWS_LONG) >= 256 * 4 * (L.LORA_MAX_ROWS_LONG // 2048)
+    assert e.value.status == -4
+    assert L.lora_segments_ws_bytes(L.LORA_MAX_ROWS_LONG) >= 12 * L.LORA_MAX_ROWS_LONG
+    assert L.lora_segments_ws_bytes(L.LORA_MAX_ROWS) < 64 * 1024
+
+
+def test_launch_counts_of_the_segment_builder():
+    assert L.lora_segments_launches(make_pool(32, 8), 1024) == 1
+    assert L.lora_segments_launches(make_pool(32, 8), 16384) == 2
+    assert L.lora_segments_launches(make_pool(256, 128), 8192) == 1
+    assert L.lora_segments_launches(make_pool(256, 128), 16385) == 6      # 15 key bits: two passes
+    assert L.lora_segments_launches(make_pool(70000, 1), 100000) == 8     # 17 key bits: three passes
+
+
+def test_one_hot_key_among_thousands_in_a_long_batch():
+    """Most of 60000 rows on one of 40000 keys: a segment that spans dozens of chunks of the sorted
+    order, next to chunks with a thousand short segments."""
+    P, n, E = 60000, 400, 100
+    rng = np.random.default_rng(78)
+    aid = rng.integers(0, n, size=P).astype(np.int32)
+    eid = rng.integers(0, E, size=P).astype(np.int32)
+    hot = rng.random(P) < 0.8
+    aid[hot], eid[hot] = 311, 42
+    aid[rng.random(P) < 0.02] = -1
+    eid[::7000] = E                          # ids outside the pool: reported and dropped
+    pool = make_pool(n, E)
+    seg = run_segments(pool, aid, eid)
+    compare(seg, aid, eid, n, E)
+    assert int(seg.status.cpu()[0]) == 2
 
 
 def test_one_hot_key_in_a_long_batch():
