@@ -134,6 +134,30 @@ class LayerRunner:
         L.lora_apply_group(dp.pool, layer, j, x, x.shape[1], None, db.seg, ys,
                            [y.shape[1] for y in ys], self.v, L.LORA_DTYPE_BF16, stream=stream)
 
-    def step(self, layer: int, stream=None):
-        self.build_segments(stream)
-        self.apply(layer, stream)
+    def step(self, layer: int, stream=None, one_call: bool = True):
+        """One layer call.  one_call: the segment build and the first application go through
+        lora_moe_build_apply / lora_build_apply_group (the library decides whether the first shrink
+        sorts the batch itself); otherwise lora_build_segments and the applications one by one."""
+        if not one_call:
+            self.build_segments(stream)
+            self.apply(layer, stream)
+            return
+        dp, db = self.dp, self.db
+        if self.moe:
+            x, mid = db.inputs["x"], db.inputs["mid"]
+            L.lora_moe_build_apply(dp.pool, layer, L.LORA_MOE_UPGATE, x, x.shape[1], db.token_of_pair,
+                                   db.adapter_id, db.expert_id, db.P, db.seg, db.y["gate"], db.y["up"],
+                                   db.y["gate"].shape[1], self.ws, stream=stream)
+            L.lora_moe_apply(dp.pool, layer, L.LORA_MOE_DOWN, mid, mid.shape[1], None, db.seg,
+                             db.y["down"], None, db.y["down"].shape[1], self.ws, stream=stream)
+        else:
+            for i, (j, c) in enumerate(self.groups):
+                if i:
+                    self.apply_group(layer, j, c, stream)
+                    continue
+                projs = dp.workload.projs[j:j + c]
+                x = db.inputs[projs[0].input]
+                ys = [db.y[p.name] for p in projs]
+                L.lora_build_apply_group(dp.pool, layer, j, x, x.shape[1], None, db.adapter_id, db.expert_id,
+                                         db.P, db.seg, ys, [y.shape[1] for y in ys], self.v,
+                                         L.LORA_DTYPE_BF16, stream=stream)

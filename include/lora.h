@@ -295,6 +295,30 @@ int lora_apply_group(const lora_pool *pool, int layer, int proj0, int n_proj, co
                      size_t ws_bytes, void *stream);
 
 /* ------------------------------------------------------------------------------------
+ * Segment build and first application of a layer call in one entry point (App. A.2.2: the
+ * rows of a batch are aggregated by adapter before shrink and expand; Sec. 5.2: scheduling
+ * the LoRA computation with few launches).
+ *
+ * lora_build_apply_group = lora_build_segments(adapter_id, expert_id, P, seg, seg_ws) followed by
+ * lora_apply_group(..., seg, ...), with the same arguments, results (segments and outputs, bit
+ * for bit) and errors; lora_moe_build_apply likewise for lora_moe_apply.  For decode batches of
+ * at most 2048 rows on pools of at most 256 (adapter, expert) keys the first shrink kernel
+ * sorts the batch itself and writes `seg` out for the calls that follow, so the launch of the
+ * segment builder, which such a short layer call feels, goes away; otherwise the two are
+ * launched one after the other.  `seg` is complete when the call's kernels have run and is
+ * then used like any other (the down projection of the same MoE layer, later groups of a
+ * dense layer).  A call that returns an error has enqueued nothing.
+ * lora_build_apply_launches: kernels such a call enqueues for P rows (host-side query).
+ * ------------------------------------------------------------------------------------ */
+int lora_build_apply_group(const lora_pool *pool, int layer, int proj0, int n_proj, const void *x,
+                           int64_t ldx, const int32_t *src_row, const int32_t *adapter_id,
+                           const int32_t *expert_id, int P, lora_segments *seg, void *seg_ws,
+                           size_t seg_ws_bytes, void *const *y, const int64_t *ldy, int out_dtype,
+                           void *ws, size_t ws_bytes, void *stream);
+
+int lora_build_apply_launches(const lora_pool *pool, int proj0, int n_proj, int out_dtype, int P);
+
+/* ------------------------------------------------------------------------------------
  * MoE application (Sec. 3: the LoRA computation runs twice per MoE layer, for the
  * up/gate and for the down projection; Sec. 4.1: a batch of b requests with top-k routing
  * activates b*k units per layer).  Rows are (token, expert) pairs.
@@ -312,6 +336,13 @@ size_t lora_moe_ws_bytes(const lora_pool *pool, int P);
 int lora_moe_apply(const lora_pool *pool, int layer, int which, const void *in, int64_t ld_in,
                    const int32_t *token_of_pair, const lora_segments *seg,
                    void *y0, void *y1, int64_t ldy, void *ws, size_t ws_bytes, void *stream);
+
+/* lora_build_segments + lora_moe_apply in one entry point; see lora_build_apply_group. */
+int lora_moe_build_apply(const lora_pool *pool, int layer, int which, const void *in,
+                         int64_t ld_in, const int32_t *token_of_pair, const int32_t *adapter_id,
+                         const int32_t *expert_id, int P, lora_segments *seg, void *seg_ws,
+                         size_t seg_ws_bytes, void *y0, void *y1, int64_t ldy, void *ws,
+                         size_t ws_bytes, void *stream);
 
 /*
  * lora_moe_apply for callers that cannot allocate device memory and have no workspace to hand

@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     lora_pool_layer_ready, lora_pool_read_unit, lora_pool_unit_layout, lora_pool_destroy,
     lora_segments_ws_bytes, lora_segments_launches, lora_build_segments, lora_v_bytes, lora_shrink, lora_expand, lora_apply,
     lora_group_ws_bytes, lora_apply_group, lora_group_launches,
+    lora_build_apply_group, lora_build_apply_launches, lora_moe_build_apply,
     lora_moe_ws_bytes, lora_moe_apply, lora_moe_apply_static, lora_moe_shrink,
     lora_moe_combine_ws_bytes, lora_moe_down_combine, lora_moe_expand, lora_strerror,
     LORA_DTYPE_BF16, LORA_DTYPE_F32, LORA_MOE_UPGATE, LORA_MOE_DOWN, LORA_MAX_ROWS, LORA_MAX_ROWS_LONG, LORA_STATIC_WS_BYTES,

@@ -24,7 +24,7 @@ EXPORTED_SYMBOLS = [
     "lora_pool_unit_layout", "lora_pool_device_table", "lora_pool_destroy",
     "lora_segments_ws_bytes", "lora_segments_launches", "lora_build_segments", "lora_v_bytes", "lora_shrink",
     "lora_provision_iar", "lora_provision_min_cache", "lora_provision_memory_bytes",
-    "lora_expand", "lora_apply", "lora_group_ws_bytes", "lora_group_launches", "lora_apply_group", "lora_moe_ws_bytes", "lora_moe_apply", "lora_moe_apply_static", "lora_moe_combine_ws_bytes", "lora_moe_down_combine", "lora_moe_shrink", "lora_moe_expand",
+    "lora_expand", "lora_apply", "lora_group_ws_bytes", "lora_group_launches", "lora_apply_group", "lora_build_apply_group", "lora_build_apply_launches", "lora_moe_ws_bytes", "lora_moe_apply", "lora_moe_build_apply", "lora_moe_apply_static", "lora_moe_combine_ws_bytes", "lora_moe_down_combine", "lora_moe_shrink", "lora_moe_expand",
 ]
 
 
@@ -129,6 +129,14 @@ def load_library():
     lib.lora_apply_group.restype = i32
     lib.lora_apply_group.argtypes = [vp, i32, i32, i32, vp, i64, vp, C.POINTER(_Segments),
                                      C.POINTER(vp), C.POINTER(i64), i32, vp, sz, vp]
+    lib.lora_build_apply_group.restype = i32
+    lib.lora_build_apply_group.argtypes = [vp, i32, i32, i32, vp, i64, vp, vp, vp, i32, C.POINTER(_Segments),
+                                           vp, sz, C.POINTER(vp), C.POINTER(i64), i32, vp, sz, vp]
+    lib.lora_build_apply_launches.restype = i32
+    lib.lora_build_apply_launches.argtypes = [vp, i32, i32, i32, i32]
+    lib.lora_moe_build_apply.restype = i32
+    lib.lora_moe_build_apply.argtypes = [vp, i32, i32, vp, i64, vp, vp, vp, i32, C.POINTER(_Segments), vp, sz,
+                                         vp, vp, i64, vp, sz, vp]
     lib.lora_moe_ws_bytes.restype = sz
     lib.lora_moe_ws_bytes.argtypes = [vp, i32]
     lib.lora_moe_apply.restype = i32
@@ -413,8 +421,38 @@ def lora_apply_group(pool, layer, proj0, x, ldx, src_row, seg: Segments, ys, ldy
            "lora_apply_group")
 
 
+def lora_build_apply_group(pool, layer, proj0, x, ldx, src_row, adapter_id, expert_id, P: int,
+                           seg: Segments, ys, ldys, ws, out_dtype=LORA_DTYPE_BF16, stream=None):
+    """lora_build_segments + lora_apply_group in one call (the first group of a layer call)."""
+    n = len(ys)
+    y_arr = (C.c_void_p * n)(*[_addr(y) for y in ys])
+    ld_arr = (C.c_int64 * n)(*[int(v) for v in ldys])
+    _check(load_library().lora_build_apply_group(
+        _h(pool), layer, proj0, n, _addr(x), ldx, _addr(src_row), _addr(adapter_id), _addr(expert_id), P,
+        C.byref(seg.c), _addr(seg.ws), seg.ws.numel(), y_arr, ld_arr, out_dtype, _addr(ws),
+        ws.numel() * ws.element_size(), _stream(stream)), "lora_build_apply_group")
+
+
+def lora_build_apply_launches(pool, proj0: int, n_proj: int, P: int, out_dtype=LORA_DTYPE_BF16) -> int:
+    rc = load_library().lora_build_apply_launches(_h(pool), proj0, n_proj, out_dtype, P)
+    if rc < 0:
+        _check(rc, "lora_build_apply_launches")
+    return int(rc)
+
+
 def lora_moe_ws_bytes(pool, P: int) -> int:
     return int(load_library().lora_moe_ws_bytes(_h(pool), P))
+
+
+def lora_moe_build_apply(pool, layer, which, inp, ld_in, token_of_pair, adapter_id, expert_id, P: int,
+                         seg: Segments, y0, y1, ldy, ws, ws_bytes=None, stream=None):
+    """lora_build_segments + lora_moe_apply in one call."""
+    if ws_bytes is None:
+        ws_bytes = ws.numel() * ws.element_size()
+    _check(load_library().lora_moe_build_apply(
+        _h(pool), layer, which, _addr(inp), ld_in, _addr(token_of_pair), _addr(adapter_id),
+        _addr(expert_id), P, C.byref(seg.c), _addr(seg.ws), seg.ws.numel(), _addr(y0), _addr(y1), ldy,
+        _addr(ws), ws_bytes, _stream(stream)), "lora_moe_build_apply")
 
 
 def lora_moe_apply(pool, layer, which, inp, ld_in, token_of_pair, seg: Segments, y0, y1, ldy,

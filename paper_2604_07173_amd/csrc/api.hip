@@ -341,13 +341,22 @@ ShrinkParams shrink_params(const lora_pool *pool, int layer, const Group &g, con
 }
 
 int do_shrink(const lora_pool *pool, int layer, const Group &g, const void *x, int64_t ldx,
-              const int32_t *src_row, const lora_segments *seg, hipStream_t st)
+              const int32_t *src_row, const lora_segments *seg, hipStream_t st,
+              const SegParams *build = nullptr)
 {
     ShrinkParams sp = shrink_params(pool, layer, g, x, ldx, src_row, seg);
     if (seg->tile_rows == kDecodeTileRows) {
+        if (build) {
+            // every workgroup sorts the batch before its first item: fewer, longer-lived workgroups
+            static const int per_cu = tune_int("LORA_INLINE_BUILD_WGS_PER_CU", 4, 1, 64);
+            sp.build = 1;
+            sp.seg = *build;
+            sp.grid = (int)std::min<int64_t>(sp.grid, (int64_t)cu_count() * per_cu);
+        }
         LORA_HIP(launch_shrink_decode(sp, st));
         return LORA_OK;
     }
+    if (build) return LORA_ERR_INVALID_ARG;       // the caller checks inline_build_ok first
     for (int j = 0; j < g.n; j += 2) {
         sp.proj0 = g.proj0 + j;
         sp.n_fused = std::min(2, g.n - j);
@@ -518,10 +527,30 @@ bool fused_plan(const lora_pool *pool, const Group &g, const lora_segments *seg,
     return true;
 }
 
-// shrink then expand of a group: one launch where that is possible, else two
-int do_apply(const lora_pool *pool, int layer, const Group &g, const void *x, int64_t ldx,
-             const int32_t *src_row, const lora_segments *seg, int out_dtype, hipStream_t st)
+// Can the shrink of this group sort the batch itself (segments_inline.h) instead of waiting for
+// a launch of the segment builder?  Small decode batches of at most 256 keys on the K-split
+// shrink kernel.
+bool inline_build_ok(const lora_pool *pool, const Group &g, const lora_segments *seg, int out_dtype)
 {
+    static const int enabled = tune_int("LORA_INLINE_BUILD", 1, 0, 1);
+    if (!enabled || seg->P <= 0 || seg->P > inline_build_max_rows() ||
+        (int64_t)pool->d.n_adapters * pool->d.n_experts > inline_build_max_keys())
+        return false;
+    if (seg->tile_rows != kDecodeTileRows || ksplit_of(pool, g.proj0, seg->P).wave_per_tile) return false;
+    return !fused_plan(pool, g, seg, out_dtype, nullptr, nullptr);
+}
+
+// shrink then expand of a group: one launch where that is possible, else two.  `build`: the
+// segments of this batch have not been built yet; the shrink does it where it can, else the
+// segment builder is launched first.
+int do_apply(const lora_pool *pool, int layer, const Group &g, const void *x, int64_t ldx,
+             const int32_t *src_row, const lora_segments *seg, int out_dtype, hipStream_t st,
+             const SegParams *build = nullptr, void *build_ws = nullptr)
+{
+    if (build && !inline_build_ok(pool, g, seg, out_dtype)) {
+        LORA_HIP(launch_segments(*build, build_ws, st));
+        build = nullptr;
+    }
     if (fused_plan(pool, g, seg, out_dtype, nullptr, nullptr)) {
         FusedParams fp;
         memset(&fp, 0, sizeof fp);
@@ -531,7 +560,7 @@ int do_apply(const lora_pool *pool, int layer, const Group &g, const void *x, in
         LORA_HIP(launch_fused_decode(fp, st));
         return LORA_OK;
     }
-    int rc = do_shrink(pool, layer, g, x, ldx, src_row, seg, st);
+    int rc = do_shrink(pool, layer, g, x, ldx, src_row, seg, st, build);
     if (rc != LORA_OK) return rc;
     return do_expand(pool, layer, g, seg, out_dtype, st);
 }
@@ -928,8 +957,9 @@ int lora_segments_launches(const lora_pool *pool, int P)
     return segments_large_handles(sp) ? segments_large_launches(sp) : 1;
 }
 
-int lora_build_segments(const lora_pool *pool, const int32_t *adapter_id, const int32_t *expert_id,
-                        int P, lora_segments *seg, void *ws, size_t ws_bytes, void *stream)
+// checks of lora_build_segments; fills the launch parameters and the host fields of `seg`
+static int prepare_segments(const lora_pool *pool, const int32_t *adapter_id, const int32_t *expert_id,
+                            int P, lora_segments *seg, void *ws, size_t ws_bytes, SegParams &sp)
 {
     int rc = check_pool(pool);
     if (rc != LORA_OK) return rc;
@@ -943,7 +973,6 @@ int lora_build_segments(const lora_pool *pool, const int32_t *adapter_id, const 
         if (!aligned(ws, 16) || !aligned(seg->tiles, 16)) return LORA_ERR_MISALIGNED;
         if (ws_bytes < lora_segments_ws_bytes(P)) return LORA_ERR_BUFFER_TOO_SMALL;
     }
-    SegParams sp;
     memset(&sp, 0, sizeof sp);
     sp.adapter_id = adapter_id;
     sp.expert_id = expert_id;
@@ -963,6 +992,15 @@ int lora_build_segments(const lora_pool *pool, const int32_t *adapter_id, const 
     seg->tile_rows = pick_tile_rows(pool, P);
     seg->n_keys = pool->d.n_adapters * pool->d.n_experts;
     seg->reserved = 0;
+    return LORA_OK;
+}
+
+int lora_build_segments(const lora_pool *pool, const int32_t *adapter_id, const int32_t *expert_id,
+                        int P, lora_segments *seg, void *ws, size_t ws_bytes, void *stream)
+{
+    SegParams sp;
+    int rc = prepare_segments(pool, adapter_id, expert_id, P, seg, ws, ws_bytes, sp);
+    if (rc != LORA_OK) return rc;
     LORA_HIP(launch_segments(sp, ws, static_cast<hipStream_t>(stream)));
     return LORA_OK;
 }
@@ -1044,9 +1082,12 @@ size_t lora_group_ws_bytes(const lora_pool *pool, int proj0, int n_proj, int P)
     return (size_t)n_proj * lora_v_bytes(pool, proj0, P);
 }
 
-int lora_apply_group(const lora_pool *pool, int layer, int proj0, int n_proj, const void *x,
-                     int64_t ldx, const int32_t *src_row, const lora_segments *seg, void *const *y,
-                     const int64_t *ldy, int out_dtype, void *ws, size_t ws_bytes, void *stream)
+// lora_apply_group; `build`: the segments are still to be built (lora_build_apply_group).  A
+// call that returns an error has enqueued nothing.
+static int apply_group_impl(const lora_pool *pool, int layer, int proj0, int n_proj, const void *x,
+                            int64_t ldx, const int32_t *src_row, const lora_segments *seg, void *const *y,
+                            const int64_t *ldy, int out_dtype, void *ws, size_t ws_bytes, void *stream,
+                            const SegParams *build, void *build_ws)
 {
     int rc = check_pool(pool);
     if (rc != LORA_OK) return rc;
@@ -1060,7 +1101,10 @@ int lora_apply_group(const lora_pool *pool, int layer, int proj0, int n_proj, co
         if (d.proj[proj0 + j].h_in != d.proj[proj0].h_in) return LORA_ERR_BAD_SHAPE;
     if (out_dtype != LORA_DTYPE_BF16 && out_dtype != LORA_DTYPE_F32) return LORA_ERR_INVALID_ARG;
     if (!y || !ldy) return LORA_ERR_INVALID_ARG;
-    if (seg->P == 0) return LORA_OK;
+    if (seg->P == 0) {
+        if (build) LORA_HIP(launch_segments(*build, build_ws, static_cast<hipStream_t>(stream)));
+        return LORA_OK;
+    }
     rc = check_act(x, ldx, d.proj[proj0].h_in, 2);
     if (rc != LORA_OK) return rc;
     if (!ws) return LORA_ERR_INVALID_ARG;
@@ -1078,7 +1122,50 @@ int lora_apply_group(const lora_pool *pool, int layer, int proj0, int n_proj, co
         g.y[j] = y[j];
         g.ldy[j] = ldy[j];
     }
-    return do_apply(pool, layer, g, x, ldx, src_row, seg, out_dtype, static_cast<hipStream_t>(stream));
+    return do_apply(pool, layer, g, x, ldx, src_row, seg, out_dtype, static_cast<hipStream_t>(stream), build,
+                    build_ws);
+}
+
+int lora_apply_group(const lora_pool *pool, int layer, int proj0, int n_proj, const void *x,
+                     int64_t ldx, const int32_t *src_row, const lora_segments *seg, void *const *y,
+                     const int64_t *ldy, int out_dtype, void *ws, size_t ws_bytes, void *stream)
+{
+    return apply_group_impl(pool, layer, proj0, n_proj, x, ldx, src_row, seg, y, ldy, out_dtype, ws, ws_bytes,
+                            stream, nullptr, nullptr);
+}
+
+int lora_build_apply_group(const lora_pool *pool, int layer, int proj0, int n_proj, const void *x,
+                           int64_t ldx, const int32_t *src_row, const int32_t *adapter_id,
+                           const int32_t *expert_id, int P, lora_segments *seg, void *seg_ws,
+                           size_t seg_ws_bytes, void *const *y, const int64_t *ldy, int out_dtype,
+                           void *ws, size_t ws_bytes, void *stream)
+{
+    SegParams sp;
+    int rc = prepare_segments(pool, adapter_id, expert_id, P, seg, seg_ws, seg_ws_bytes, sp);
+    if (rc != LORA_OK) return rc;
+    return apply_group_impl(pool, layer, proj0, n_proj, x, ldx, src_row, seg, y, ldy, out_dtype, ws, ws_bytes,
+                            stream, &sp, seg_ws);
+}
+
+int lora_build_apply_launches(const lora_pool *pool, int proj0, int n_proj, int out_dtype, int P)
+{
+    int rc = check_pool(pool);
+    if (rc != LORA_OK) return rc;
+    if (n_proj < 1 || n_proj > kMaxFused || proj0 < 0 || proj0 + n_proj > pool->d.n_proj || P < 0)
+        return LORA_ERR_BAD_SHAPE;
+    lora_segments seg;
+    memset(&seg, 0, sizeof seg);
+    seg.P = P;
+    seg.tile_rows = pick_tile_rows(pool, P);
+    seg.n_keys = pool->d.n_adapters * pool->d.n_experts;
+    Group g;
+    memset(&g, 0, sizeof g);
+    g.proj0 = proj0;
+    g.n = n_proj;
+    if (P == 0) return 1;
+    const int apply = seg.tile_rows == kDecodeTileRows ? (fused_plan(pool, g, &seg, out_dtype, nullptr, nullptr) ? 1 : 2)
+                                                       : (n_proj + 1) / 2 + 2;
+    return apply + (inline_build_ok(pool, g, &seg, out_dtype) ? 0 : lora_segments_launches(pool, P));
 }
 
 int lora_group_launches(const lora_pool *pool, int proj0, int n_proj, int out_dtype,
@@ -1226,19 +1313,45 @@ int lora_moe_apply_static(const lora_pool *pool, int layer, int which, const voi
                           kStaticScratchBytes, stream);
 }
 
-int lora_moe_apply(const lora_pool *pool, int layer, int which, const void *in, int64_t ld_in,
-                   const int32_t *token_of_pair, const lora_segments *seg, void *y0, void *y1,
-                   int64_t ldy, void *ws, size_t ws_bytes, void *stream)
+static int moe_apply_impl(const lora_pool *pool, int layer, int which, const void *in, int64_t ld_in,
+                          const int32_t *token_of_pair, const lora_segments *seg, void *y0, void *y1,
+                          int64_t ldy, void *ws, size_t ws_bytes, void *stream, const SegParams *build,
+                          void *build_ws)
 {
     int rc = moe_common_checks(pool, layer, which, seg, ws, ws_bytes);
-    if (rc != LORA_OK || seg->P == 0) return rc;
+    if (rc != LORA_OK) return rc;
+    if (seg->P == 0) {
+        if (build) LORA_HIP(launch_segments(*build, build_ws, static_cast<hipStream_t>(stream)));
+        return LORA_OK;
+    }
     rc = moe_shrink_checks(pool, which, in, ld_in, token_of_pair);
     if (rc != LORA_OK) return rc;
     rc = moe_expand_checks(pool, which, y0, y1, ldy);
     if (rc != LORA_OK) return rc;
     return do_apply(pool, layer, moe_group(pool, which, seg, ws, y0, y1, ldy), in, ld_in,
                     which == LORA_MOE_UPGATE ? token_of_pair : nullptr, seg, LORA_DTYPE_BF16,
-                    static_cast<hipStream_t>(stream));
+                    static_cast<hipStream_t>(stream), build, build_ws);
+}
+
+int lora_moe_apply(const lora_pool *pool, int layer, int which, const void *in, int64_t ld_in,
+                   const int32_t *token_of_pair, const lora_segments *seg, void *y0, void *y1,
+                   int64_t ldy, void *ws, size_t ws_bytes, void *stream)
+{
+    return moe_apply_impl(pool, layer, which, in, ld_in, token_of_pair, seg, y0, y1, ldy, ws, ws_bytes, stream,
+                          nullptr, nullptr);
+}
+
+int lora_moe_build_apply(const lora_pool *pool, int layer, int which, const void *in, int64_t ld_in,
+                         const int32_t *token_of_pair, const int32_t *adapter_id,
+                         const int32_t *expert_id, int P, lora_segments *seg, void *seg_ws,
+                         size_t seg_ws_bytes, void *y0, void *y1, int64_t ldy, void *ws, size_t ws_bytes,
+                         void *stream)
+{
+    SegParams sp;
+    int rc = prepare_segments(pool, adapter_id, expert_id, P, seg, seg_ws, seg_ws_bytes, sp);
+    if (rc != LORA_OK) return rc;
+    return moe_apply_impl(pool, layer, which, in, ld_in, token_of_pair, seg, y0, y1, ldy, ws, ws_bytes, stream,
+                          &sp, seg_ws);
 }
 
 size_t lora_moe_combine_ws_bytes(const lora_pool *pool, int P)

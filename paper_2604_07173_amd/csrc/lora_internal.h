@@ -114,6 +114,8 @@ struct ShrinkParams {
     int rank;
     int grid;
     int wave_per_tile;       // decode kernel: every wave takes a whole tile (no K split across waves)
+    int build;               // decode kernel: the segments are built inside the launch, from `seg`
+    SegParams seg;
 };
 
 struct ExpandParams {
@@ -174,6 +176,8 @@ hipError_t launch_set_adapter(Unit *table, int n_layers, int n_adapters, int per
 hipError_t launch_segments(const SegParams &p, void *ws, hipStream_t s);
 hipError_t launch_segments_large(const SegParams &p, void *ws, hipStream_t s);
 size_t segments_large_ws_bytes(int P);
+int inline_build_max_rows();      // limits of the segment build inside the decode shrink
+int inline_build_max_keys();
 bool segments_large_handles(const SegParams &p);    // does the multi-workgroup builder take this batch?
 int segments_large_launches(const SegParams &p);    // kernels it enqueues for it
 hipError_t launch_shrink(const ShrinkParams &p, hipStream_t s);

@@ -16,6 +16,9 @@
 // Rank 8: a packed block holds 64 K values (two 32-deep halves side by side in the 16 M
 // rows), is multiplied once with each half's x values, and rows 0..7 of the first product
 // plus rows 8..15 of the second give the eight rank entries.
+#include <type_traits>
+
+#include "segments_inline.h"
 #include "shrink_wave.h"
 
 namespace lora {
@@ -25,7 +28,11 @@ namespace {
 // tiles, units and counts are passed again as restrict-qualified kernel arguments: with a
 // uniform index the compiler then reads them through the scalar cache, which shortens the
 // dependent chain tile -> unit -> first data load.
-template <int R, int NPROJ, bool NT, bool WPT>
+//
+// BUILD: the segments are not there yet; every workgroup sorts the batch for itself in LDS
+// first (segments_inline.h) and takes tile records and row indices from there, and workgroup 0
+// writes them out for the launches that follow.
+template <int R, int NPROJ, bool NT, bool WPT, bool BUILD = false>
 __global__ __launch_bounds__(256, 2) void shrink16_kernel(ShrinkParams p,
                                                           const lora_tile *__restrict__ tiles,
                                                           const Unit *__restrict__ units,
@@ -33,7 +40,14 @@ __global__ __launch_bounds__(256, 2) void shrink16_kernel(ShrinkParams p,
 {
     using Wave = ShrinkWave<R, NPROJ, NT>;
     constexpr int NACC = Wave::NACC, KU = Wave::KU;
-    __shared__ f32x4 red[WPT ? 1 : 4][NPROJ][NACC][WPT ? 1 : 64];
+    static_assert(!(BUILD && WPT), "the build needs the whole workgroup");
+    union Scratch {                   // the build's counts are dead before the first sums are added
+        f32x4 red[WPT ? 1 : 4][NPROJ][NACC][WPT ? 1 : 64];
+        std::conditional_t<BUILD, InlineCounts, char> counts;
+    };
+    __shared__ Scratch scratch;
+    __shared__ std::conditional_t<BUILD, InlineSegments, char> built;
+    auto &red = scratch.red;
 
     const int tid = threadIdx.x, wave = tid >> 6;
     Wave w;
@@ -41,7 +55,13 @@ __global__ __launch_bounds__(256, 2) void shrink16_kernel(ShrinkParams p,
     w.g = w.lane >> 4;
     w.i16 = w.lane & 15;
     w.h_in = p.h_in;
-    const int n_tiles = counts[2];
+    int n_tiles;
+    if constexpr (BUILD) {
+        build_segments_inline(p.seg, scratch.counts, built, blockIdx.x == 0);   // `built` is complete behind its last barrier
+        n_tiles = built.n_tiles;
+    } else {
+        n_tiles = counts[2];
+    }
     const int n_items = n_tiles * p.n_parts;
     const int kblocks = (p.h_in + KU - 1) / KU;
 
@@ -51,20 +71,24 @@ __global__ __launch_bounds__(256, 2) void shrink16_kernel(ShrinkParams p,
     for (int item = first; item < n_items; item += stride) {
         const int tile_ix = item / p.n_parts;
         const int part = item - tile_ix * p.n_parts;
-        const lora_tile t = tiles[tile_ix];
+        lora_tile t;
+        if constexpr (BUILD) t = built.tiles[tile_ix];
+        else t = tiles[tile_ix];
 #pragma unroll
         for (int pj = 0; pj < NPROJ; ++pj)
             w.Ap[pj] = units[(int64_t)t.key * p.n_proj + p.proj0 + pj].A;
         w.row_ok = w.i16 < t.n_rows;
         {
-            int s = p.perm[t.row0 + min(w.i16, t.n_rows - 1)];
+            int s;
+            if constexpr (BUILD) s = built.perm[t.row0 + min(w.i16, t.n_rows - 1)];
+            else s = p.perm[t.row0 + min(w.i16, t.n_rows - 1)];
             if (p.src_row) s = p.src_row[s];
             w.xp = p.x + (int64_t)s * p.ldx;
         }
         const int part_begin = part * p.kb_per_part;
         const int part_end = min(part_begin + p.kb_per_part, kblocks);
 
-        if (WPT) {
+        if constexpr (WPT) {
             w.run(part_begin, part_end);
             // lane (row i16, group g) holds rank entries 4g..4g+3 of its row; for rank 8 the
             // entries of groups 2,3 belong to the second half product and are added to the
@@ -127,7 +151,12 @@ __global__ __launch_bounds__(256, 2) void shrink16_kernel(ShrinkParams p,
 template <int R, int NPROJ>
 hipError_t launch_rn(const ShrinkParams &p, hipStream_t s)
 {
-    if (p.wave_per_tile)
+    if (p.build) {
+        if (p.wave_per_tile || p.seg.P > kInlineMaxRows || p.seg.n_adapters * (int64_t)p.seg.n_experts > kInlineMaxKeys)
+            return hipErrorInvalidValue;
+        hipLaunchKernelGGL((shrink16_kernel<R, NPROJ, true, false, true>), dim3(p.grid), dim3(256), 0, s, p,
+                           p.tiles, p.units, p.counts);
+    } else if (p.wave_per_tile)
         hipLaunchKernelGGL((shrink16_kernel<R, NPROJ, true, true>), dim3(p.grid), dim3(256), 0, s, p,
                            p.tiles, p.units, p.counts);
     else
@@ -148,6 +177,9 @@ hipError_t launch_r(const ShrinkParams &p, hipStream_t s)
 }
 
 }  // namespace
+
+int inline_build_max_rows() { return kInlineMaxRows; }
+int inline_build_max_keys() { return kInlineMaxKeys; }
 
 hipError_t launch_shrink_decode(const ShrinkParams &p, hipStream_t s)
 {
