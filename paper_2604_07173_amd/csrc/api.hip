@@ -528,16 +528,18 @@ bool fused_plan(const lora_pool *pool, const Group &g, const lora_segments *seg,
 }
 
 // Can the shrink of this group sort the batch itself (segments_inline.h) instead of waiting for
-// a launch of the segment builder?  Small decode batches of at most 256 keys on the K-split
-// shrink kernel.
+// a launch of the segment builder?  Small decode batches of at most 256 keys, on the K-split
+// shrink kernel or on the kernel that runs shrink and expand as one launch (the whole call of a
+// small batch is then a single launch).
 bool inline_build_ok(const lora_pool *pool, const Group &g, const lora_segments *seg, int out_dtype)
 {
     static const int enabled = tune_int("LORA_INLINE_BUILD", 1, 0, 1);
     if (!enabled || seg->P <= 0 || seg->P > inline_build_max_rows() ||
         (int64_t)pool->d.n_adapters * pool->d.n_experts > inline_build_max_keys())
         return false;
-    if (seg->tile_rows != kDecodeTileRows || ksplit_of(pool, g.proj0, seg->P).wave_per_tile) return false;
-    return !fused_plan(pool, g, seg, out_dtype, nullptr, nullptr);
+    if (seg->tile_rows != kDecodeTileRows) return false;
+    // the one-launch kernel and the K-split shrink can; the wave-per-tile shrink cannot
+    return fused_plan(pool, g, seg, out_dtype, nullptr, nullptr) || !ksplit_of(pool, g.proj0, seg->P).wave_per_tile;
 }
 
 // shrink then expand of a group: one launch where that is possible, else two.  `build`: the
@@ -557,6 +559,10 @@ int do_apply(const lora_pool *pool, int layer, const Group &g, const void *x, in
         fp.s = shrink_params(pool, layer, g, x, ldx, src_row, seg);
         expand_params(pool, layer, g, seg, out_dtype, fp.e);
         fused_plan(pool, g, seg, out_dtype, &fp.s, &fp.e);
+        if (build) {
+            fp.s.build = 1;
+            fp.s.seg = *build;
+        }
         LORA_HIP(launch_fused_decode(fp, st));
         return LORA_OK;
     }

@@ -129,9 +129,12 @@ struct ExpandWave {
 
 // vlds: null = v comes from the K parts in global memory (p.v[pj]); otherwise the tile's summed v
 // already sits in LDS as [16][R] floats (the kernel that runs shrink and expand in one launch).
+// perm_lds: null = the sorted order comes from p.perm; otherwise from LDS (the kernel that also
+// builds the segments).
 template <int R, bool F32, int NI, bool OVW>
 __device__ inline void expand_item(const ExpandParams &p, const lora_tile &t, const Unit &unit, int pj,
-                                   int c0, int c1, int lane, const float *vlds = nullptr)
+                                   int c0, int c1, int lane, const float *vlds = nullptr,
+                                   const uint16_t *perm_lds = nullptr)
 {
     using Tile = ExpandTile<R>;
     constexpr int KS = Tile::KS, KV = Tile::KV, ESZ = F32 ? 4 : 2;
@@ -146,7 +149,8 @@ __device__ inline void expand_item(const ExpandParams &p, const lora_tile &t, co
     for (int i = 0; i < NI; ++i) {
         const int r = 4 * i + w.g;                       // row of result register i
         w.rok[i] = r < t.n_rows;
-        const int dst = p.perm[t.row0 + min(r, t.n_rows - 1)];
+        const int at = t.row0 + min(r, t.n_rows - 1);
+        const int dst = perm_lds ? (int)perm_lds[at] : p.perm[at];       // wave-uniform choice
         w.yrow[i] = static_cast<char *>(p.y[pj]) + (int64_t)dst * p.ldy[pj] * ESZ;
     }
 
@@ -236,13 +240,14 @@ __device__ inline void expand_item(const ExpandParams &p, const lora_tile &t, co
 // quads is picked here (wave-uniform)
 template <int R, bool F32, bool OVW>
 __device__ inline void expand_tile_chunks(const ExpandParams &p, const lora_tile &t, const Unit &unit,
-                                          int pj, int c0, int c1, int lane, const float *vlds = nullptr)
+                                          int pj, int c0, int c1, int lane, const float *vlds = nullptr,
+                                          const uint16_t *perm_lds = nullptr)
 {
     switch ((t.n_rows + 3) >> 2) {
-    case 1: expand_item<R, F32, 1, OVW>(p, t, unit, pj, c0, c1, lane, vlds); break;
-    case 2: expand_item<R, F32, 2, OVW>(p, t, unit, pj, c0, c1, lane, vlds); break;
-    case 3: expand_item<R, F32, 3, OVW>(p, t, unit, pj, c0, c1, lane, vlds); break;
-    default: expand_item<R, F32, 4, OVW>(p, t, unit, pj, c0, c1, lane, vlds); break;
+    case 1: expand_item<R, F32, 1, OVW>(p, t, unit, pj, c0, c1, lane, vlds, perm_lds); break;
+    case 2: expand_item<R, F32, 2, OVW>(p, t, unit, pj, c0, c1, lane, vlds, perm_lds); break;
+    case 3: expand_item<R, F32, 3, OVW>(p, t, unit, pj, c0, c1, lane, vlds, perm_lds); break;
+    default: expand_item<R, F32, 4, OVW>(p, t, unit, pj, c0, c1, lane, vlds, perm_lds); break;
     }
 }
 

@@ -19,7 +19,10 @@
 // Sums are formed in a fixed order, so results are bit-identical run to run.  The K range is
 // split over the waves differently from the two-launch path (which also splits it over
 // workgroups), so the two paths agree to fp32 rounding, not bit for bit.
+#include <type_traits>
+
 #include "expand_item.h"
+#include "segments_inline.h"
 #include "shrink_wave.h"
 
 namespace lora {
@@ -28,7 +31,10 @@ namespace {
 
 constexpr int kFusedWaves = 4;      // waves of a workgroup (eight or sixteen measured no faster)
 
-template <int R>
+// BUILD: the segments are not there yet either; every workgroup sorts the batch for itself in LDS
+// first (segments_inline.h), workgroup 0 writes the segments out, and the whole layer call of a
+// small batch is this one launch.
+template <int R, bool BUILD>
 __global__ __launch_bounds__(64 * kFusedWaves) void fused16_kernel(FusedParams p,
                                                          const lora_tile *__restrict__ tiles,
                                                          const Unit *__restrict__ units,
@@ -36,8 +42,15 @@ __global__ __launch_bounds__(64 * kFusedWaves) void fused16_kernel(FusedParams p
 {
     using Wave = ShrinkWave<R, 1, false>;
     constexpr int NACC = Wave::NACC, KU = Wave::KU;
-    __shared__ f32x4 red[kFusedWaves][NACC][64];
+    static_assert(64 * kFusedWaves == kInlineThreads, "the build is written for this workgroup size");
+    union Scratch {                   // the build's counts are dead before the first sums are added
+        f32x4 red[kFusedWaves][NACC][64];
+        std::conditional_t<BUILD, InlineCounts, char> counts;
+    };
+    __shared__ Scratch scratch;
+    __shared__ std::conditional_t<BUILD, InlineSegments, char> built;
     __shared__ __attribute__((aligned(16))) float vsh[kDecodeTileRows * R];
+    auto &red = scratch.red;
 
     const ShrinkParams &sp = p.s;
     const ExpandParams &ep = p.e;
@@ -47,7 +60,15 @@ __global__ __launch_bounds__(64 * kFusedWaves) void fused16_kernel(FusedParams p
     w.g = w.lane >> 4;
     w.i16 = w.lane & 15;
     w.h_in = sp.h_in;
-    const int n_tiles = counts[2];
+    int n_tiles;
+    const uint16_t *perm_lds = nullptr;
+    if constexpr (BUILD) {
+        build_segments_inline(sp.seg, scratch.counts, built, blockIdx.x == 0);   // `built` is complete behind its last barrier
+        n_tiles = built.n_tiles;
+        perm_lds = built.perm;
+    } else {
+        n_tiles = counts[2];
+    }
     const int per_tile = ep.slice0[ep.n_fused];                  // workgroup items of one tile
     const int n_items = n_tiles * per_tile;
     const int kblocks = (sp.h_in + KU - 1) / KU;
@@ -58,14 +79,18 @@ __global__ __launch_bounds__(64 * kFusedWaves) void fused16_kernel(FusedParams p
         const int rem = item - tile_ix * per_tile;
         const int pj = (rem >= ep.slice0[1] ? 1 : 0) + (ep.n_fused > 2 && rem >= ep.slice0[2] ? 1 : 0);
         const int slice = rem - ep.slice0[pj];
-        const lora_tile t = tiles[tile_ix];
+        lora_tile t;
+        if constexpr (BUILD) t = built.tiles[tile_ix];
+        else t = tiles[tile_ix];
         const Unit unit = units[(int64_t)t.key * sp.n_proj + sp.proj0 + pj];
 
         // ---- shrink: this tile, this projection, the whole K range over the four waves ----------
         w.Ap[0] = unit.A;
         w.row_ok = w.i16 < t.n_rows;
         {
-            int s = sp.perm[t.row0 + min(w.i16, t.n_rows - 1)];
+            int s;
+            if constexpr (BUILD) s = built.perm[t.row0 + min(w.i16, t.n_rows - 1)];
+            else s = sp.perm[t.row0 + min(w.i16, t.n_rows - 1)];
             if (sp.src_row) s = sp.src_row[s];
             w.xp = sp.x + (int64_t)s * sp.ldx;
         }
@@ -99,7 +124,7 @@ __global__ __launch_bounds__(64 * kFusedWaves) void fused16_kernel(FusedParams p
             const int s0 = slice * cps, s1 = min(s0 + cps, ep.n_chunks[pj]);
             const int per = ((((s1 - s0) + kFusedWaves - 1) / kFusedWaves) + 1) & ~1;
             const int c0 = s0 + wave * per, c1 = min(c0 + per, s1);
-            if (c0 < c1) expand_tile_chunks<R, false, false>(ep, t, unit, pj, c0, c1, w.lane, vsh);
+            if (c0 < c1) expand_tile_chunks<R, false, false>(ep, t, unit, pj, c0, c1, w.lane, vsh, perm_lds);
         }
         __syncthreads();              // vsh and red are reused by the next item
     }
@@ -108,8 +133,15 @@ __global__ __launch_bounds__(64 * kFusedWaves) void fused16_kernel(FusedParams p
 template <int R>
 hipError_t launch_r(const FusedParams &p, hipStream_t s)
 {
-    hipLaunchKernelGGL((fused16_kernel<R>), dim3(p.s.grid), dim3(64 * kFusedWaves), 0, s, p, p.s.tiles, p.s.units,
-                       p.s.counts);
+    if (p.s.build) {
+        if (p.s.seg.P > kInlineMaxRows || p.s.seg.n_adapters * (int64_t)p.s.seg.n_experts > kInlineMaxKeys)
+            return hipErrorInvalidValue;
+        hipLaunchKernelGGL((fused16_kernel<R, true>), dim3(p.s.grid), dim3(64 * kFusedWaves), 0, s, p, p.s.tiles,
+                           p.s.units, p.s.counts);
+    } else {
+        hipLaunchKernelGGL((fused16_kernel<R, false>), dim3(p.s.grid), dim3(64 * kFusedWaves), 0, s, p, p.s.tiles,
+                           p.s.units, p.s.counts);
+    }
     return hipGetLastError();
 }
 

@@ -73,7 +73,7 @@ def test_moe_layer_call_with_the_build_inside(rank, h, f, n, E, k, tokens, inlin
     launches = L.lora_build_apply_launches(dp.pool, 0, 2, P)
     fused = L.lora_group_launches(dp.pool, 0, 2, P, seg) == 1
     if fused:
-        assert launches == 2                            # builder + one launch for shrink and expand
+        assert launches == (1 if inline else 2)         # build, shrink and expand in a single launch
     else:
         assert launches == (2 if inline else 3)
     compare(seg, b.adapter_id, b.expert_id, n, E)
@@ -99,6 +99,22 @@ def test_dense_layer_call_with_the_build_inside():
     compare(seg, b.adapter_id, None, 100, 1)
     for p in projs:
         assert np.array_equal(got[p.name], ref[p.name]), p.name
+
+
+def test_small_dense_call_is_a_single_launch():
+    """A batch small enough for shrink and expand in one launch: with the build inside, the whole
+    call (segments, shrink, expand) is one kernel."""
+    projs = (W.Proj("p", 1032, 392, "x"),)
+    w = W.Workload("t", "dense", 5, 1, 1, 8, projs, 70, "zipf", 0.8)
+    b, ws, dp, got, ref, seg = run_both(w, 16)
+    assert L.lora_build_apply_launches(dp.pool, 0, 1, 70) == 1
+    compare(seg, b.adapter_id, None, 5, 1)
+    # the same arithmetic as the call on segments built before: bit-identical
+    assert np.array_equal(got["p"], ref["p"])
+    res = oracle_projection(b, ws, 1, 0)
+    delta = W.bf16_bits_to_f32(got["p"]).astype(np.float64) - W.bf16_bits_to_f32(b.y_in["p"]).astype(np.float64)
+    act = b.adapter_id >= 0
+    assert np.linalg.norm(delta[act] - res.delta[act]) <= 0.25 * np.linalg.norm(res.delta[act]) + 1e-6
 
 
 def test_ids_outside_the_pool_are_reported_and_dropped():
