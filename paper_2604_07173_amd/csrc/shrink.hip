@@ -8,7 +8,11 @@
 // copies the packed A blocks of the first tile's (adapter, expert) into one of two LDS
 // buffers while the previous stage is being multiplied; every wave gathers the x rows of its
 // own tile (the next stage's rows are in flight during the current stage's MFMAs) and reads
-// its MFMA operands from LDS with 16-byte reads that are contiguous per wave.  A group whose
+// its MFMA operands from LDS with 16-byte reads that are contiguous per wave.  The x rows are
+// fetched as whole cache lines, four rows x 256 bytes per instruction, and turned into the MFMA
+// operand layout (16 rows x 64 bytes per operand) through 4 KiB of LDS per wave: fetching them
+// in the operand layout directly costs the address path twice the line look-ups, which a
+// load-only probe of the two streams puts at 32 against 27 us for the prefill workload.  A group whose
 // tiles do not all belong to one (adapter, expert) (a segment boundary inside the group) takes
 // a plain path in which every wave reads its own A from global memory.  Every wave owns its rows for the
 // whole K part, so there is no cross-wave reduction; lora_expand adds the K parts in a fixed
@@ -40,7 +44,12 @@ __global__ __launch_bounds__(256, 2) void shrink_long_kernel(ShrinkParams p,
     constexpr int LOADS = STAGE / 256;                 // per thread and stage
     constexpr int SUB = kTileRows / 16;
     static_assert(STAGE % 256 == 0, "a stage is copied by whole workgroup passes");
-    __shared__ u32x4 lds[2][STAGE];
+    static_assert(kStageKB == 4, "a stage of x is 256 bytes per row: the transposition below is written for that");
+    // dynamic LDS: two stages of A, then per wave 4 KiB in which a sub-tile's stage of x is
+    // turned from the layout it is fetched in (whole lines per row) into the MFMA operand layout
+    extern __shared__ __attribute__((aligned(16))) unsigned char dyn_lds[];
+    u32x4 (*lds)[STAGE] = reinterpret_cast<u32x4 (*)[STAGE]>(dyn_lds);
+    u32x4 *xt = reinterpret_cast<u32x4 *>(dyn_lds + 2 * STAGE * sizeof(u32x4)) + (threadIdx.x >> 6) * 256;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = lane >> 4, i16 = lane & 15;
@@ -84,6 +93,22 @@ __global__ __launch_bounds__(256, 2) void shrink_long_kernel(ShrinkParams p,
             xp[sub] = p.x + (int64_t)s * p.ldx + g * 8;
         }
 
+        // the same rows as they are fetched on the shared-A path: one instruction reads four
+        // rows (lane group g) x 256 contiguous bytes (16 lanes x 16 bytes), i.e. whole cache
+        // lines, which the address path serves faster than 16 rows x 64 bytes
+        const uint16_t *xq[SUB][4];
+        bool qv[SUB][4];
+#pragma unroll
+        for (int sub = 0; sub < SUB; ++sub)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int r = sub * 16 + j * 4 + g;
+                qv[sub][j] = live && r < t.n_rows;
+                int s = p.perm[t.row0 + min(r, t.n_rows - 1)];
+                if (p.src_row) s = p.src_row[s];
+                xq[sub][j] = p.x + (int64_t)s * p.ldx;            // start of the row
+            }
+
         const int kb_begin = part * p.kb_per_part;
         const int kb_end = min(kb_begin + p.kb_per_part, kblocks);
         const int n_stages = (kb_end - kb_begin + kStageKB - 1) / kStageKB;
@@ -115,18 +140,36 @@ __global__ __launch_bounds__(256, 2) void shrink_long_kernel(ShrinkParams p,
 #pragma unroll
             for (int i = 0; i < LOADS; ++i) buf[(4 * i + wave) * 64 + lane] = a[i];
         };
-        auto load_x = [&](int kb0, u32x4 (&xv)[SUB][kStageKB]) {
+        // a stage of x as whole lines: lane (g, i16) of instruction j holds K values
+        // kb0 * 32 + 8 * i16 .. + 7 of row 4 j + g of the sub-tile
+        auto load_rows = [&](int kb0, u32x4 (&xr)[SUB][4]) {
+            const int kb = kb0 + (i16 >> 2);                  // the K block this lane's 16 bytes belong to
+            const bool k_ok = kb < kb_end;
+            const bool c_ok = k_ok && kb0 * kKBlock + i16 * 8 < p.h_in;
+            const int c = c_ok ? kb0 * kKBlock + i16 * 8 : 0;    // beyond the part: the row's first bytes, not used
 #pragma unroll
             for (int sub = 0; sub < SUB; ++sub)
 #pragma unroll
-                for (int kbi = 0; kbi < kStageKB; ++kbi) {
-                    const bool k_ok = kb0 + kbi < kb_end;
-                    const int kb = k_ok ? kb0 + kbi : kb_end - 1;
-                    const bool c_ok = k_ok && kb * kKBlock + g * 8 < p.h_in;
-                    const int c = c_ok ? kb * kKBlock : 0;
-                    const u32x4 v = ld16<true>(xp[sub] + c);      // read once: nontemporal
-                    xv[sub][kbi] = (c_ok && rv[sub]) ? v : zero4;
+                for (int j = 0; j < 4; ++j) {
+                    const u32x4 v = ld16<true>(xq[sub][j] + c);  // read once: nontemporal
+                    xr[sub][j] = (c_ok && qv[sub][j]) ? v : zero4;
                 }
+        };
+        // rows -> MFMA operands through this wave's 4 KiB of LDS.  The 16-byte column of a row
+        // is stored at column (col ^ row): the writes of an instruction (one row per 16 lanes)
+        // and the reads (16 rows, one column each per 16 lanes) both touch every bank once.
+        // LDS operations of one wave execute in order, so no barrier is needed.
+        auto to_operands = [&](const u32x4 (&xr)[SUB][4], u32x4 (&xv)[SUB][kStageKB]) {
+#pragma unroll
+            for (int sub = 0; sub < SUB; ++sub) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int row = j * 4 + g;
+                    xt[row * 16 + (i16 ^ row)] = xr[sub][j];
+                }
+#pragma unroll
+                for (int kbi = 0; kbi < kStageKB; ++kbi) xv[sub][kbi] = xt[i16 * 16 + ((kbi * 4 + g) ^ i16)];
+            }
         };
         // one stage out of LDS: straight-line code, no global loads inside
         auto compute = [&](const u32x4 *buf, const u32x4 (&xv)[SUB][kStageKB]) {
@@ -144,29 +187,24 @@ __global__ __launch_bounds__(256, 2) void shrink_long_kernel(ShrinkParams p,
                     }
         };
 
-        u32x4 x0[SUB][kStageKB], x1[SUB][kStageKB];
         if (same_key) {
             u32x4 areg[LOADS];
+            u32x4 xr[SUB][4];                  // the next stage's x as fetched
+            u32x4 xc[SUB][kStageKB];           // the current stage's x as MFMA operands
             load_a(kb_begin, areg);
-            load_x(kb_begin, x0);
+            load_rows(kb_begin, xr);
             store_a(areg, lds[0]);
+            to_operands(xr, xc);
             __syncthreads();
-            for (int s = 0; s < n_stages; s += 2) {
+            for (int s = 0; s < n_stages; ++s) {
                 const int kb0 = kb_begin + s * kStageKB;
-                load_a(kb0 + kStageKB, areg);
-                load_x(kb0 + kStageKB, x1);
+                load_a(kb0 + kStageKB, areg);                 // beyond the part: zeros, never multiplied
+                load_rows(kb0 + kStageKB, xr);
                 __builtin_amdgcn_sched_barrier(0);            // all of the next stage's loads first
-                compute(lds[0], x0);
-                store_a(areg, lds[1]);
+                compute(lds[s & 1], xc);
+                store_a(areg, lds[(s + 1) & 1]);
+                to_operands(xr, xc);
                 __syncthreads();
-                if (s + 1 < n_stages) {                       // uniform over the workgroup
-                    load_a(kb0 + 2 * kStageKB, areg);
-                    load_x(kb0 + 2 * kStageKB, x0);
-                    __builtin_amdgcn_sched_barrier(0);
-                    compute(lds[1], x1);
-                    store_a(areg, lds[0]);
-                    __syncthreads();
-                }
             }
         } else {
             // a segment boundary inside the group: every wave reads the A of its own tile from
@@ -207,16 +245,23 @@ __global__ __launch_bounds__(256, 2) void shrink_long_kernel(ShrinkParams p,
     }
 }
 
+template <int R, int NPROJ>
+hipError_t launch_rn(const ShrinkParams &p, hipStream_t s)
+{
+    // two stages of A (kStageKB K blocks of NPROJ * R / 16 operand blocks of 1 KiB) + 4 KiB per wave
+    constexpr int kLds = 2 * kStageKB * NPROJ * (R / 16) * 1024 + 4 * 4096;
+    static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(shrink_long_kernel<R, NPROJ>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
+    if (attr != hipSuccess) return attr;
+    hipLaunchKernelGGL((shrink_long_kernel<R, NPROJ>), dim3(p.grid), dim3(256), kLds, s, p, p.tiles, p.units,
+                       p.counts);
+    return hipGetLastError();
+}
+
 template <int R>
 hipError_t launch_r(const ShrinkParams &p, hipStream_t s)
 {
-    if (p.n_fused == 2)
-        hipLaunchKernelGGL((shrink_long_kernel<R, 2>), dim3(p.grid), dim3(256), 0, s, p, p.tiles, p.units,
-                           p.counts);
-    else
-        hipLaunchKernelGGL((shrink_long_kernel<R, 1>), dim3(p.grid), dim3(256), 0, s, p, p.tiles, p.units,
-                           p.counts);
-    return hipGetLastError();
+    return p.n_fused == 2 ? launch_rn<R, 2>(p, s) : launch_rn<R, 1>(p, s);
 }
 
 }  // namespace
