@@ -22,6 +22,11 @@
 //    indices of sub-tile q+2 are being fetched.  All loads are unconditional (rows beyond a
 //    tile re-read a valid row and are not stored), so the code is straight-line.
 //
+// The base-output rows are read and written with nontemporal accesses: every byte of y is touched
+// once, and keeping it out of the caches leaves them to the B tiles and operand images that many
+// waves share (prefill workload: 250 -> 229 us; in the decode kernel, where a tile's rows are few
+// and B is the larger stream, the same change costs 5 %).
+//
 // Row placement as in the decode kernel: tile row r of a sub-tile sits in MFMA row slot
 // (r % 4) * 4 + r / 4, so result register i of lane group g is row 4*i + g and each y
 // access of a wave covers four rows x 256 contiguous bytes.
@@ -144,7 +149,7 @@ struct LongWave {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
-            for (int h = 0; h < NY; ++h) d.y[i][h] = ld16<false>(r.y[i] + 16 * h);
+            for (int h = 0; h < NY; ++h) d.y[i][h] = ld16<true>(r.y[i] + 16 * h);     // touched once: nontemporal
     }
 
     __device__ inline void compute_store(const Rows &r, const Data &d, const typename Tile::B &b) const
@@ -162,8 +167,8 @@ struct LongWave {
                     o1[q] = __float_as_uint(__uint_as_float(d.y[i][NY - 1][q]) + acc[4 + q][i]);
                 }
                 if (r.ok[i]) {
-                    st16<false>(r.y[i], o0);
-                    st16<false>(r.y[i] + 16, o1);
+                    st16<true>(r.y[i], o0);
+                    st16<true>(r.y[i] + 16, o1);
                 }
             } else {
                 u32x4 o;
@@ -174,7 +179,7 @@ struct LongWave {
                     const float f1 = __uint_as_float(u & 0xFFFF0000u) + acc[2 * q + 1][i];
                     o[q] = pack_bf16_rne(f0, f1);
                 }
-                if (r.ok[i]) st16<false>(r.y[i], o);
+                if (r.ok[i]) st16<true>(r.y[i], o);
             }
         }
     }
