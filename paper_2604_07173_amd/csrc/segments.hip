@@ -383,11 +383,11 @@ __global__ __launch_bounds__(kThreads) void segments_kernel(SegParams p)
 //
 // Longer batches are launched with several workgroups.  Steps 1 and 2 up to the list of
 // segments are repeated by every one of them (a workgroup cannot hand anything to another inside
-// a launch, and repeating costs no time); the segment records and tiles, step 3 and step 4 are
-// shared out by segment index: workgroup g of G takes the segments [S g / G, S (g + 1) / G),
+// a launch, and repeating costs no time); the list of segments with the keys' starts, the segment
+// records and tiles, step 3 and step 4 are shared out by segment index: workgroup g of G takes the segments [S g / G, S (g + 1) / G),
 // which are a contiguous range of keys and of sorted positions.  Measured on the fine-grained MoE
-// shapes (8192 rows, 32768 keys): one workgroup 15.3 us, of which 7.1 us are the shared-out
-// steps; eight workgroups 12.9 us.  If the radix path has to run, workgroup 0 runs it.
+// shapes (8192 rows, 32768 keys): one workgroup 15.3 us, of which 9.6 us are the shared-out
+// steps; eight workgroups 11.4 us.  If the radix path has to run, workgroup 0 runs it.
 //
 // Two 16-bit counters share a 32-bit LDS word (a batch has at most 16384 rows, so neither
 // half overflows and positions fit 16 bits).  The words are skewed by one word per
@@ -455,6 +455,7 @@ __global__ __launch_bounds__(NT) void segments_bucket_kernel(SegParams p)
     const unsigned w0 = (unsigned)tid << SHIFT;       // my counter words: w0 .. w0 + WPT - 1
     unsigned rs_before, rs_total, t_before, t_total;  // rows | segments << 16, and tiles
     unsigned cw[WPT];                                 // my words (two 16-bit counts each)
+    unsigned segs_mine;                               // occupied keys among mine
     {
         unsigned rows = 0, tiles = 0, mx = 0, segs = 0;
 #pragma unroll
@@ -467,6 +468,7 @@ __global__ __launch_bounds__(NT) void segments_bucket_kernel(SegParams p)
             mx = max(mx, max(lo, hi));
             segs += (lo ? 1u : 0u) + (hi ? 1u : 0u);
         }
+        segs_mine = segs;
         if (kFallback && mx > kMaxBucket) atomicMax(&longest, mx);
         // a batch has at most 16384 rows, so rows and segments share a word
         block_excl_sum2<NW>(rows | (segs << 16), tiles, wave_sums, &rs_before, &t_before, &rs_total,
@@ -482,7 +484,13 @@ __global__ __launch_bounds__(NT) void segments_bucket_kernel(SegParams p)
     const int P_act = (int)(rs_total & 0xFFFFu);
     const int S = (int)(rs_total >> 16);
     const int n_tiles = (int)t_total;
-    {
+    // From here on workgroup wg takes the segments [s0, s1), i.e. the keys [key_lo, key_hi) and the
+    // sorted positions [pos_lo, pos_hi); up to here every workgroup has done the same.
+    const int s0 = (int)((int64_t)S * wg / G), s1 = (int)((int64_t)S * (wg + 1) / G);
+    // Only the threads whose keys lie in or next to that range go on: the others' segments are
+    // listed, and their keys' counts turned into starts, by the workgroups that need them.
+    const int seg_first = (int)(rs_before >> 16);
+    if (seg_first <= s1 && seg_first + (int)segs_mine >= s0) {
         // list of the occupied keys with the first tile of each, and the start of every key in
         // place of its count (all from the words in registers: nothing is read back)
         int sidx = (int)(rs_before >> 16);
@@ -506,9 +514,6 @@ __global__ __launch_bounds__(NT) void segments_bucket_kernel(SegParams p)
         }
     }
     __syncthreads();
-    // Up to here every workgroup has done the same; from here on workgroup wg takes the segments
-    // [s0, s1), i.e. the keys [key_lo, key_hi) and the sorted positions [pos_lo, pos_hi).
-    const int s0 = (int)((int64_t)S * wg / G), s1 = (int)((int64_t)S * (wg + 1) / G);
     const unsigned key_lo = s0 < S ? seglist[s0] & 0xFFFFu : 0x10000u;
     const unsigned key_hi = s1 < S ? seglist[s1] & 0xFFFFu : 0x10000u;
     const int pos_lo = s0 < S ? (int)half_of(key_lo) : P_act;
