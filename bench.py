@@ -344,15 +344,21 @@ def copy_ceiling_gbs():
 
 
 def kernel_sources_digest():
-    """Digest of the kernel sources the library is built from: a counter summary under profiles/
-    names the digest it was taken with, so a summary of other kernels is recognised as stale."""
+    """Digest of the kernel sources the library is built from (comments and white space left
+    out): a counter summary under profiles/ names the digest it was taken with, so a summary of
+    other kernels is recognised as stale."""
     import hashlib
+    import re
     h = hashlib.sha256()
     csrc = os.path.join(ROOT, "paper_2604_07173_amd", "csrc")
     for fn in sorted(os.listdir(csrc)):
         if fn.endswith((".hip", ".h")):
+            text = open(os.path.join(csrc, fn), "r", errors="replace").read()
+            # the code only: comments and layout do not change what the kernels do
+            text = re.sub(r"/\*.*?\*/", " ", text, flags=re.S)
+            text = re.sub(r"//[^\n]*", " ", text)
             h.update(fn.encode())
-            h.update(open(os.path.join(csrc, fn), "rb").read())
+            h.update(" ".join(text.split()).encode())
     return h.hexdigest()[:16]
 
 
