@@ -110,9 +110,9 @@ __global__ __launch_bounds__(256, 2) void shrink16_kernel(ShrinkParams p,
                 }
             }
         } else {
-            const int kb_per_wave = (p.kb_per_part + 3) >> 2;
-            const int kb_begin = part_begin + wave * kb_per_wave;
-            w.run(kb_begin, min(kb_begin + kb_per_wave, part_end));
+            // the four waves take the part's steps in turn, so that together they read a
+            // contiguous kilobyte or more of every x row (and of A) at about the same time
+            w.run(part_begin + wave * Wave::KB, part_end, 4 * Wave::KB);
 
             // add the four waves' sums in a fixed order and store this part of v
 #pragma unroll

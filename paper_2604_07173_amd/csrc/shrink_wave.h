@@ -84,8 +84,9 @@ struct ShrinkWave {
             }
     }
 
-    // K units [kb_begin, kb_end), two steps in flight
-    __device__ inline void run(int kb_begin, int kb_end)
+    // K units kb_begin, kb_begin + stride, ... below kb_end in steps of KB units (stride = KB:
+    // the contiguous range [kb_begin, kb_end)), two steps in flight
+    __device__ inline void run(int kb_begin, int kb_end, int stride = KB)
     {
 #pragma unroll
         for (int pj = 0; pj < NPROJ; ++pj)
@@ -95,14 +96,14 @@ struct ShrinkWave {
         Step s0, s1;
         load(kb_begin, kb_end, s0);
         int kb0 = kb_begin;
-        for (; kb0 + 2 * KB < kb_end; kb0 += 2 * KB) {
-            load(kb0 + KB, kb_end, s1);
+        for (; kb0 + 2 * stride < kb_end; kb0 += 2 * stride) {
+            load(kb0 + stride, kb_end, s1);
             mma(s0);
-            load(kb0 + 2 * KB, kb_end, s0);
+            load(kb0 + 2 * stride, kb_end, s0);
             mma(s1);
         }
-        if (kb0 + KB < kb_end) {
-            load(kb0 + KB, kb_end, s1);
+        if (kb0 + stride < kb_end) {
+            load(kb0 + stride, kb_end, s1);
             mma(s0);
             mma(s1);
         } else {

@@ -225,6 +225,17 @@ def test_long_segment_kernels_with_many_short_segments(rank, y_mode):
         check_accumulate(got, res, f"long kernels, short segments r{rank}")
 
 
+@pytest.mark.parametrize("tokens,tile_rows", [(6143, 16), (6144, 32), (2048, 16)])
+def test_kernel_family_switch_for_long_decode_batches(tokens, tile_rows):
+    """Between 24 and 64 rows per key the 32-row-tile kernels are taken only from 6144 rows on:
+    both sides of that limit, 128 keys, against the oracle (all rows)."""
+    w = W.Workload("t", "dense", 128, 1, 1, 16, (W.Proj("p", 264, 136, "x"),), tokens, "zipf", 0.6)
+    b, ws, got, (dp, db, run) = run_dense(w, 52, "zero", drop=0.02)
+    assert db.seg.c.tile_rows == tile_rows
+    res = oracle_projection(b, ws, 0, 0)
+    check_delta(W.bf16_bits_to_f32(got).astype(np.float64), res.delta, f"family switch {tokens}")
+
+
 @pytest.mark.parametrize("tokens", [1, 40, 5000])
 def test_batch_without_any_adapter_leaves_everything_untouched(tokens):
     """Every row has id -1: no segment, no tile; y keeps its bits (both kernel families)."""
