@@ -159,7 +159,7 @@ __device__ inline void expand_item(const ExpandParams &p, const lora_tile &t, co
     // chunks' weights and base output, so that the wait for v leaves those in flight; a part
     // beyond the last re-reads the last one and counts as zero.  The parts are added in
     // ascending order.
-    constexpr int PB = R <= 32 ? 4 : 2;                          // parts per batch of loads
+    constexpr int PB = R <= 32 ? 4 : (F32 ? 1 : 2);              // parts per batch of loads (registers permitting)
     const int row = (w.i16 & 3) * 4 + (w.i16 >> 2);
     const bool valid = row < t.n_rows;
     const float *vrow = p.v[pj] + (int64_t)(t.row0 + (valid ? row : 0)) * R;
