@@ -225,6 +225,24 @@ def test_long_segment_kernels_with_many_short_segments(rank, y_mode):
         check_accumulate(got, res, f"long kernels, short segments r{rank}")
 
 
+@pytest.mark.parametrize("y_mode", ["zero", "normal"])
+@pytest.mark.parametrize("rank,h_in,h_out", [(16, 40, 8), (64, 72, 136), (32, 264, 520), (16, 136, 1032), (64, 2056, 72)])
+def test_long_segment_kernels_at_ragged_widths(rank, h_in, h_out, y_mode):
+    """The 32-row-tile kernels at widths that are not whole stages of 128 K values nor whole
+    chunks of 128 columns (the shrink fetches x a stage of whole lines at a time): 3 adapters,
+    400 rows, every row against the oracle."""
+    w = dense_workload(rank, h_in, h_out, n=3, tokens=400)
+    b, ws, got, (dp, db, run) = run_dense(w, 53, y_mode, drop=0.03)
+    assert db.seg.c.tile_rows == 32
+    res = oracle_projection(b, ws, 0, 0)
+    if y_mode == "zero":
+        check_delta(W.bf16_bits_to_f32(got).astype(np.float64), res.delta, f"long ragged r{rank} {h_in}x{h_out}")
+    else:
+        check_accumulate(got, res, f"long ragged r{rank} {h_in}x{h_out}")
+    none = b.adapter_id < 0
+    assert np.array_equal(got[none], b.y_in["p"][none])
+
+
 @pytest.mark.parametrize("tokens,tile_rows", [(6143, 16), (6144, 32), (2048, 16)])
 def test_kernel_family_switch_for_long_decode_batches(tokens, tile_rows):
     """Between 24 and 64 rows per key the 32-row-tile kernels are taken only from 6144 rows on:
