@@ -117,6 +117,40 @@ def test_small_dense_call_is_a_single_launch():
     assert np.linalg.norm(delta[act] - res.delta[act]) <= 0.25 * np.linalg.norm(res.delta[act]) + 1e-6
 
 
+def test_random_batches_through_the_one_call_entry_point():
+    """Sixty random batches (1 to 2048 rows, 1 to 256 keys, uniform or skewed ids, rows without
+    adapter) through lora_build_apply_group on a narrow projection: segments against the oracle,
+    outputs bit-identical to lora_build_segments + lora_apply_group.  Small ones run as a single
+    launch, the others build inside the shrink."""
+    rng = np.random.default_rng(2025)
+    single = inside = 0
+    for case in range(60):
+        n = int(rng.choice([1, 2, 5, 16, 64, 200, 256]))
+        P = int(rng.choice([1, 3, 16, 17, 63, 64, 65, 255, 257, 700, 1024, 1500, 2047, 2048]))
+        alpha = float(rng.choice([0.0, 0.7, 1.3]))
+        ids = "uniform" if alpha == 0.0 else "zipf"
+        w = W.Workload("t", "dense", n, 1, 1, 8, (W.Proj("p", 40, 24, "x"),), P, ids, alpha)
+        b = W.make_batch(w, 1000 + case, y_mode="normal", no_adapter_frac=float(rng.choice([0.0, 0.1, 0.6])))
+        ws = W.make_weights(w, 1000 + case, bank_elems=1 << 18)
+        dp, db = DevicePool(ws, b.scale), DeviceBatch(b)
+        run = LayerRunner(dp, db)
+        launches = L.lora_build_apply_launches(dp.pool, 0, 1, P)
+        assert launches in (1, 2)
+        single += launches == 1
+        inside += launches == 2
+        poison_segments(db.seg)
+        run.step(0, one_call=True)
+        torch.cuda.synchronize()
+        got = bits_from_dev(db.y["p"])
+        compare(db.seg, b.adapter_id, None, n, 1)
+        db.seg = L.Segments(db.P)
+        db.reset_y()
+        run.step(0, one_call=False)
+        torch.cuda.synchronize()
+        assert np.array_equal(got, bits_from_dev(db.y["p"])), (case, n, P)
+    assert single >= 5 and inside >= 5
+
+
 def test_ids_outside_the_pool_are_reported_and_dropped():
     projs = (W.Proj("gate", 264, 392, "x"), W.Proj("up", 264, 392, "x"), W.Proj("down", 392, 264, "mid"))
     w = W.Workload("t", "moe", 8, 4, 2, 16, projs, 200, "uniform")
