@@ -64,7 +64,10 @@ CASES = [
     (21, 16385, 257, 1, 0.0), (22, 32768, 256, 128, 0.0), (23, 40000, 300, 7, 0.1),
     (24, 100000, 70000, 1, 0.02), (25, 65536 + 2049, 3, 30000, 0.0), (26, 30000, 600, 500, 0.0),
     (27, 20000, 300, 300, 1.0), (28, 262144 + 5, 512, 128, 0.01),
+    # the largest batch the library takes (LORA_MAX_ROWS_LONG rows): one pass, and three passes
+    (29, 1 << 20, 16, 1, 0.0), (30, 1 << 20, 1000, 100, 0.01),
 ]
+assert CASES[-1][1] == L.LORA_MAX_ROWS_LONG
 
 
 @pytest.mark.parametrize("seed,P,n,E,drop", CASES)
