@@ -22,6 +22,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
+COLD_SETS = 8           # copies of the activation buffers of the cold-activation measurement
 
 
 def parse_args():
@@ -42,6 +43,14 @@ def parse_args():
                     help="MoE workloads: replace the down application (update added to every pair's "
                          "row) by lora_moe_down_combine (routing-weighted sum into token rows); "
                          "a variant for comparison, not the headline")
+    ap.add_argument("--activation-sets", type=int, default=1,
+                    help="rotate the steps over this many copies of the batch's device buffers (ids, "
+                         "activations, base outputs): with enough copies no activation byte of a "
+                         "step is still in a cache when the step comes round again")
+    ap.add_argument("--activation-policy", choices=["auto", "resident", "streaming"], default="auto",
+                    help="lora_pool_set_activation_policy for the pool of the run")
+    ap.add_argument("--no-cold-activations", action="store_true",
+                    help="skip the extra measurement over rotated copies of the activation buffers")
     ap.add_argument("--tokens", type=int, default=0,
                     help="run the workload's shapes with another number of tokens (0 = as defined)")
     ap.add_argument("--steps-only", action="store_true",
@@ -159,12 +168,20 @@ def measure(name, args, steps, warmup, with_cpu_baseline):
     b = W.make_batch(w, args.seed, y_mode="normal")
     ws = W.make_weights(w, args.seed, n_layers=n_layers)
     dp = DevicePool(ws, b.scale)
+    policies = {"auto": L.LORA_ACT_AUTO, "resident": L.LORA_ACT_RESIDENT, "streaming": L.LORA_ACT_STREAMING}
+    policy = policies[getattr(args, "activation_policy", "auto")]
+    L.lora_pool_set_activation_policy(dp.pool, policy)
     db = DeviceBatch(b)
     run = LayerRunner(dp, db)
     acct = W.algorithmic_bytes(w, b.adapter_id, b.expert_id)
     phases = make_phases(L, W, dp, db, run, acct, getattr(args, "down_combine", False) and w.kind == "moe")
 
     combine = getattr(args, "down_combine", False) and w.kind == "moe"
+
+    n_sets = 1 if combine else max(1, getattr(args, "activation_sets", 1))
+    runs = [run]
+    for _ in range(n_sets - 1):
+        runs.append(LayerRunner(dp, DeviceBatch(b)))
 
     def step(it):
         # the calls a server makes for one layer: lora_build_segments, then lora_moe_apply for
@@ -176,7 +193,7 @@ def measure(name, args, steps, warmup, with_cpu_baseline):
             for ph in phases:
                 ph.fn(layer)
         else:
-            run.step(layer)
+            runs[it % n_sets].step(layer)
 
     # ---- whole-step throughput ----------------------------------------------------------
     for it in range(warmup):
@@ -259,6 +276,44 @@ def measure(name, args, steps, warmup, with_cpu_baseline):
         bytes2 = W.algorithmic_bytes(w, b2.adapter_id, b2.expert_id)["total"]
         del lanes, run2, db2
 
+    # ---- the same steps over rotated copies of the batch's device buffers: the timed steps above
+    # reuse one set of buffers, so their activations (not the weights, which rotate over layers)
+    # are still in the 256 MiB memory-side cache when a step comes round again, as they are when
+    # the kernel before the call has just written them.  With kColdSets copies they are not.
+    # Measured under the run's policy and under LORA_ACT_STREAMING, the policy meant for that case.
+    cold = None
+    if n_sets == 1 and not combine and not getattr(args, "no_cold_activations", False) \
+            and args.launch == "graph":
+        cold_runs = [LayerRunner(dp, DeviceBatch(b)) for _ in range(COLD_SETS)]
+
+        def cold_ms(pol):
+            L.lora_pool_set_activation_policy(dp.pool, pol)
+            for it in range(COLD_SETS):
+                cold_runs[it].step(it % n_layers)
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                for it in range(steps):
+                    cold_runs[it % COLD_SETS].step((warmup + it) % n_layers)
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            ms = []
+            for _ in range(3):
+                t0 = time.perf_counter()
+                g.replay()
+                torch.cuda.synchronize()
+                ms.append((time.perf_counter() - t0) * 1e3 / steps)
+            del g
+            return sorted(ms)[1]
+
+        cold = dict(sets=COLD_SETS, ms_per_step=cold_ms(policy),
+                    ms_per_step_streaming_policy=cold_ms(L.LORA_ACT_STREAMING))
+        L.lora_pool_set_activation_policy(dp.pool, policy)
+        del cold_runs
+        torch.cuda.empty_cache()
+
     # ---- spread over the steps: an event between consecutive steps (stream launches; the
     # event records add a little to every step, so the median sits above ms_per_step) -------
     n_ev = min(steps, 200)
@@ -313,11 +368,11 @@ def measure(name, args, steps, warmup, with_cpu_baseline):
                        hbm_frac_of_peak=(total_bytes + bytes2) / 2 / (two_ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS),
         algorithmic_bytes=int(total_bytes), segments=acct["S"], pairs=acct["P_act"],
         layers_in_pool=n_layers, pool_gib=dp.nbytes / 2 ** 30, phases=per_phase, roofline=roofline,
-        launches_per_step=launches)
+        launches_per_step=launches, cold_activations=cold)
 
     if with_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(w, b, ws)
-    del dp, db, run
+    del dp, db, run, runs
     torch.cuda.empty_cache()
     return res
 
@@ -548,6 +603,7 @@ def main():
                    "launch": "one HIP graph of all timed steps" if args.launch == "graph"
                    else "stream launches",
                    "seed": args.seed, "segments": main_res["segments"], "rows": main_res["pairs"],
+                   "activation_policy": args.activation_policy,
                    **({"down": "lora_moe_down_combine (token rows)"} if args.down_combine else {})},
         "graph_replays_ms_per_step_min_median_max": spread(main_res["replay_ms"]),
         "stream_launch_ms_per_step": round(main_res["stream_ms_per_step"], 5),
@@ -571,6 +627,13 @@ def main():
             "tokens_per_s": round(main_res["two_calls"]["tokens_per_s"], 1),
             "hbm_frac_of_peak": round(main_res["two_calls"]["hbm_frac_of_peak"], 4),
             "note": "two independent layer calls on two streams; not the headline"}
+    if main_res.get("cold_activations"):
+        c = main_res["cold_activations"]
+        out["cold_activations"] = {
+            "buffer_sets": c["sets"], "ms_per_step": round(c["ms_per_step"], 5),
+            "ms_per_step_streaming_policy": round(c["ms_per_step_streaming_policy"], 5),
+            "note": "steps rotate over copies of the activation buffers, so no activation is "
+                    "cache-resident when its step starts; not the headline"}
     if "cpu_baseline" in main_res:
         out["cpu_baseline"] = main_res["cpu_baseline"]
     if args.all:
@@ -592,6 +655,11 @@ def main():
                            "phases": {k: {"us": round(v["us"], 2), "GB/s": round(v["gbs"], 1)}
                                       for k, v in r["phases"].items()},
                            "roofline": r["roofline"]}
+            if r.get("cold_activations"):
+                c = r["cold_activations"]
+                extra[name]["cold_activations_ms_per_step"] = round(c["ms_per_step"], 5)
+                extra[name]["cold_activations_ms_per_step_streaming_policy"] = round(
+                    c["ms_per_step_streaming_policy"], 5)
             if "cpu_baseline" in r:
                 extra[name]["cpu_baseline"] = r["cpu_baseline"]
         extra["adapter_load_mixtral"] = measure_adapter_load(args)

@@ -51,6 +51,13 @@ enum {
     LORA_MAX_ROWS_LONG = 1 << 20    /* rows of a batch, any pool */
 };
 
+/* where a pool's calls expect the activations (input rows, output rows) when a call starts */
+enum {
+    LORA_ACT_AUTO = 0,       /* in a cache unless a call's rows are too many to be (default) */
+    LORA_ACT_RESIDENT = 1,   /* always in a cache: no streaming hints on activations */
+    LORA_ACT_STREAMING = 2   /* in HBM only: output rows are read and written with streaming hints */
+};
+
 /* bits of the device status word written by lora_build_segments */
 enum { LORA_STATUS_BAD_ADAPTER = 1u, LORA_STATUS_BAD_EXPERT = 2u };
 
@@ -154,6 +161,27 @@ size_t lora_pool_adapter_layer_bytes(const lora_pool *pool, int adapter);
  * below the pool rank, which is exact).
  */
 int lora_pool_set_adapter(lora_pool *pool, int adapter, int rank, float scale, void *stream);
+
+/*
+ * Cache hints for the activations of this pool's compute calls (Sec. 5.2: the kernels are bound
+ * by memory traffic, so where the rows come from decides their speed).  The adapter weights are
+ * always read with streaming hints (each is read once per call).  Activations, by `policy`:
+ *   LORA_ACT_AUTO (default)  input and output rows go through the caches, as suits rows that
+ *       the kernel before the call has just written and the kernel after it will read; input
+ *       rows that every pair reads for itself (no src_row / token_of_pair gather) are streamed
+ *       once they reach 64 MiB per call, output rows once a call's outputs reach 256 MiB (the
+ *       memory-side cache holds 256 MiB).
+ *   LORA_ACT_RESIDENT        no streaming hint on any activation, whatever its size.
+ *   LORA_ACT_STREAMING       for callers whose activations are in HBM only when a call starts
+ *       (arrived over a link, or written long ago): output rows are read and written with
+ *       streaming hints at every size; input rows as under LORA_ACT_AUTO.
+ * Results are bit-identical under all three; only the decode kernels (tiles of at most 16 rows)
+ * look at the policy, the long-segment kernels always stream their outputs.  Host state only:
+ * takes effect from the next call on, must not race with calls on the same pool.  Errors:
+ * LORA_ERR_NOT_REGISTERED, LORA_ERR_INVALID_ARG (unknown policy).
+ */
+int lora_pool_set_activation_policy(lora_pool *pool, int policy);
+int lora_pool_activation_policy(const lora_pool *pool);   /* the current policy, negative on error */
 int lora_pool_load_adapter_async(lora_pool *pool, int adapter, const void *host_src,
                                  void *staging, size_t staging_bytes, void *load_stream);
 int lora_pool_wait_layer(const lora_pool *pool, int adapter, int layer, void *stream);

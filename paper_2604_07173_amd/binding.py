@@ -12,6 +12,7 @@ from typing import Optional, Sequence
 
 LORA_DTYPE_BF16, LORA_DTYPE_F32 = 0, 1
 LORA_MOE_UPGATE, LORA_MOE_DOWN = 0, 1
+LORA_ACT_AUTO, LORA_ACT_RESIDENT, LORA_ACT_STREAMING = 0, 1, 2
 LORA_MAX_PROJ = 8
 LORA_MAX_ROWS = 1 << 14
 LORA_MAX_ROWS_LONG = 1 << 20
@@ -20,7 +21,7 @@ LORA_STATIC_WS_BYTES = 16 << 20
 EXPORTED_SYMBOLS = [
     "lora_strerror", "lora_last_hip_error", "lora_pool_bytes", "lora_register_pool",
     "lora_pool_load_unit", "lora_pool_load_adapter_layer", "lora_pool_adapter_layer_bytes",
-    "lora_pool_load_adapter_async", "lora_pool_set_adapter", "lora_pool_wait_layer", "lora_pool_layer_ready", "lora_pool_read_unit",
+    "lora_pool_load_adapter_async", "lora_pool_set_adapter", "lora_pool_set_activation_policy", "lora_pool_activation_policy", "lora_pool_wait_layer", "lora_pool_layer_ready", "lora_pool_read_unit",
     "lora_pool_unit_layout", "lora_pool_device_table", "lora_pool_destroy",
     "lora_segments_ws_bytes", "lora_segments_launches", "lora_build_segments", "lora_v_bytes", "lora_shrink",
     "lora_provision_iar", "lora_provision_min_cache", "lora_provision_memory_bytes",
@@ -94,6 +95,10 @@ def load_library():
     lib.lora_pool_load_adapter_async.argtypes = [vp, i32, vp, vp, C.c_size_t, vp]
     lib.lora_pool_set_adapter.restype = i32
     lib.lora_pool_set_adapter.argtypes = [vp, i32, i32, C.c_float, vp]
+    lib.lora_pool_set_activation_policy.restype = i32
+    lib.lora_pool_set_activation_policy.argtypes = [vp, i32]
+    lib.lora_pool_activation_policy.restype = i32
+    lib.lora_pool_activation_policy.argtypes = [vp]
     lib.lora_pool_wait_layer.restype = i32
     lib.lora_pool_wait_layer.argtypes = [vp, i32, i32, vp]
     lib.lora_pool_layer_ready.restype = i32
@@ -293,6 +298,17 @@ def lora_pool_load_adapter_async(pool, adapter, host_src, staging, load_stream=N
         _h(pool), adapter, _addr(host_src), _addr(staging),
         staging.numel() * staging.element_size(), _stream(load_stream)),
         "lora_pool_load_adapter_async")
+
+
+def lora_pool_set_activation_policy(pool, policy):
+    _check(load_library().lora_pool_set_activation_policy(_h(pool), int(policy)),
+           "lora_pool_set_activation_policy")
+
+
+def lora_pool_activation_policy(pool) -> int:
+    rc = load_library().lora_pool_activation_policy(_h(pool))
+    _check(min(rc, 0), "lora_pool_activation_policy")
+    return rc
 
 
 def lora_pool_set_adapter(pool, adapter, rank, scale, stream=None):

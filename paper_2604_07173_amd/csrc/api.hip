@@ -122,6 +122,7 @@ struct lora_pool {
     size_t B_off[LORA_MAX_PROJ], B_bytes[LORA_MAX_PROJ];
     std::vector<Unit> table;              // host mirror of the device table
     std::vector<hipEvent_t> ready;        // [adapter][layer], created at the first async load
+    int act_policy;                       // LORA_ACT_*: cache hints of the activation streams
 
     size_t unit_base(int layer, int adapter, int expert) const
     {
@@ -305,6 +306,27 @@ size_t parts_bytes(const lora_pool *pool, int n_parts, int P)
 
 // launch parameters of the shrink of a group (decode kernels: complete; long kernels: all but
 // the per-launch projection fields)
+// Cache hints of the activation streams (the weights are always streamed: they are read once).
+// x rows that every pair reads for itself (no gather through src_row) are read exactly once, so
+// keeping them cacheable pays only while they are small against the memory-side cache: a quarter
+// of it and more is streamed, so that it does not push out the output rows, which are read,
+// written and read again by whatever runs next.  Output rows are streamed when the caller says
+// its activations are not in a cache when a call starts (LORA_ACT_STREAMING), or when one call's
+// outputs exceed the memory-side cache anyway.  LORA_ACT_RESIDENT switches both off.
+bool stream_x(const lora_pool *pool, const int32_t *src_row, int64_t x_bytes)
+{
+    static const int mb = tune_int("LORA_X_STREAM_MB", kStreamXMiB, 1, 1 << 20);
+    if (pool->act_policy == LORA_ACT_RESIDENT || src_row) return false;
+    return x_bytes >= (int64_t)mb << 20;
+}
+
+bool stream_y(const lora_pool *pool, int64_t y_bytes)
+{
+    static const int mb = tune_int("LORA_Y_STREAM_MB", kStreamYMiB, 1, 1 << 20);
+    if (pool->act_policy == LORA_ACT_RESIDENT) return false;
+    return pool->act_policy == LORA_ACT_STREAMING || y_bytes >= (int64_t)mb << 20;
+}
+
 ShrinkParams shrink_params(const lora_pool *pool, int layer, const Group &g, const void *x, int64_t ldx,
                            const int32_t *src_row, const lora_segments *seg)
 {
@@ -332,6 +354,7 @@ ShrinkParams shrink_params(const lora_pool *pool, int layer, const Group &g, con
         sp.n_fused = g.n;
         for (int j = 0; j < g.n; ++j) sp.v[j] = g.v[j];
         sp.wave_per_tile = ks.wave_per_tile;
+        sp.x_stream = !ks.wave_per_tile && stream_x(pool, src_row, (int64_t)seg->P * pd.h_in * 2);
         const int64_t wgs = ks.wave_per_tile ? (items + 3) / 4 : items;
         sp.grid = (int)std::min<int64_t>(wgs, (int64_t)cu_count() * per_cu);
         return sp;
@@ -354,6 +377,7 @@ int do_shrink(const lora_pool *pool, int layer, const Group &g, const void *x, i
             // every workgroup sorts the batch before its first item: fewer, longer-lived workgroups
             static const int per_cu = tune_int("LORA_INLINE_BUILD_WGS_PER_CU", 4, 1, 64);
             sp.build = 1;
+            sp.x_stream = 0;                      // at most 2048 rows: nothing to stream
             sp.seg = *build;
             sp.grid = (int)std::min<int64_t>(sp.grid, (int64_t)cu_count() * per_cu);
         }
@@ -415,6 +439,12 @@ int expand_params(const lora_pool *pool, int layer, const Group &g, const lora_s
         ep.proj0 = g.proj0;
         ep.n_fused = g.n;
         ep.overwrite = g.overwrite && out_dtype == LORA_DTYPE_BF16;
+        {
+            int64_t y_bytes = 0;
+            for (int j = 0; j < g.n; ++j)
+                y_bytes += (int64_t)seg->P * pool->d.proj[g.proj0 + j].h_out * (ep.out_f32 ? 4 : 2);
+            ep.y_stream = stream_y(pool, y_bytes);
+        }
         int64_t chunks_per_tile = 0;
         for (int j = 0; j < g.n; ++j) chunks_per_tile += chunks_of(pool->d.proj[g.proj0 + j].h_out);
         const int64_t units = tub * chunks_per_tile;
@@ -647,6 +677,7 @@ int lora_register_pool(const lora_pool_desc *d, void *slab, size_t slab_bytes,
     lora_pool *p = new (std::nothrow) lora_pool();
     if (!p) return LORA_ERR_INVALID_ARG;
     p->magic = kPoolMagic;
+    p->act_policy = LORA_ACT_AUTO;
     p->d = *d;
     p->scale.assign(d->n_adapters, 1.0f);
     if (d->scale) p->scale.assign(d->scale, d->scale + d->n_adapters);
@@ -805,6 +836,22 @@ int lora_pool_set_adapter(lora_pool *pool, int adapter, int rank, float scale, v
             u.scale = scale;
         }
     return LORA_OK;
+}
+
+int lora_pool_set_activation_policy(lora_pool *pool, int policy)
+{
+    int rc = check_pool(pool);
+    if (rc != LORA_OK) return rc;
+    if (policy != LORA_ACT_AUTO && policy != LORA_ACT_RESIDENT && policy != LORA_ACT_STREAMING)
+        return LORA_ERR_INVALID_ARG;
+    pool->act_policy = policy;
+    return LORA_OK;
+}
+
+int lora_pool_activation_policy(const lora_pool *pool)
+{
+    int rc = check_pool(pool);
+    return rc != LORA_OK ? rc : pool->act_policy;
 }
 
 size_t lora_pool_adapter_layer_bytes(const lora_pool *pool, int adapter)

@@ -12,7 +12,7 @@ namespace {
 // tiles, units and counts are passed again as restrict-qualified kernel arguments: with a
 // wave-uniform index the compiler then reads them through the scalar cache, which shortens
 // the dependent chain tile -> unit -> first data load.
-template <int R, bool F32, bool OVW>
+template <int R, bool F32, bool OVW, bool YNT>
 __global__ __launch_bounds__(256, 2) void expand16_kernel(ExpandParams p,
                                                           const lora_tile *__restrict__ tiles,
                                                           const Unit *__restrict__ units,
@@ -43,21 +43,27 @@ __global__ __launch_bounds__(256, 2) void expand16_kernel(ExpandParams p,
         if (c0 >= c1) continue;
         const lora_tile t = tiles[tile_ix];
         const Unit unit = units[(int64_t)t.key * p.n_proj + p.proj0 + pj];
-        expand_tile_chunks<R, F32, OVW>(p, t, unit, pj, c0, c1, lane);
+        expand_tile_chunks<R, F32, OVW, YNT>(p, t, unit, pj, c0, c1, lane);
     }
+}
+
+template <int R, bool YNT>
+hipError_t launch_ry(const ExpandParams &p, hipStream_t s)
+{
+    const dim3 block(p.waves * 64);
+    if (p.out_f32)
+        hipLaunchKernelGGL((expand16_kernel<R, true, false, YNT>), dim3(p.grid), block, 0, s, p, p.tiles, p.units, p.counts);
+    else if (p.overwrite)
+        hipLaunchKernelGGL((expand16_kernel<R, false, true, YNT>), dim3(p.grid), block, 0, s, p, p.tiles, p.units, p.counts);
+    else
+        hipLaunchKernelGGL((expand16_kernel<R, false, false, YNT>), dim3(p.grid), block, 0, s, p, p.tiles, p.units, p.counts);
+    return hipGetLastError();
 }
 
 template <int R>
 hipError_t launch_r(const ExpandParams &p, hipStream_t s)
 {
-    const dim3 block(p.waves * 64);
-    if (p.out_f32)
-        hipLaunchKernelGGL((expand16_kernel<R, true, false>), dim3(p.grid), block, 0, s, p, p.tiles, p.units, p.counts);
-    else if (p.overwrite)
-        hipLaunchKernelGGL((expand16_kernel<R, false, true>), dim3(p.grid), block, 0, s, p, p.tiles, p.units, p.counts);
-    else
-        hipLaunchKernelGGL((expand16_kernel<R, false, false>), dim3(p.grid), block, 0, s, p, p.tiles, p.units, p.counts);
-    return hipGetLastError();
+    return p.y_stream ? launch_ry<R, true>(p, s) : launch_ry<R, false>(p, s);
 }
 
 }  // namespace

@@ -28,7 +28,9 @@ namespace lora {
 
 // OVW: the output rows are written, not updated: the base output counts as zero and is never
 // read (used when the update goes to a buffer of its own rather than into base rows).
-template <int R, bool F32, int NI, bool OVW>
+// YNT: the output rows are read and written with the streaming hint (for callers whose outputs
+// are not in a cache when the call starts, or are too large to be).
+template <int R, bool F32, int NI, bool OVW, bool YNT = false>
 struct ExpandWave {
     using Tile = ExpandTile<R>;
     static constexpr int KS = Tile::KS;
@@ -54,7 +56,7 @@ struct ExpandWave {
         for (int i = 0; i < NI; ++i)
 #pragma unroll
             for (int q = 0; q < NY; ++q)
-                y.r[i][q] = OVW ? u32x4{0u, 0u, 0u, 0u} : ld16<false>(yrow[i] + (int64_t)colc * ESZ + 16 * q);
+                y.r[i][q] = OVW ? u32x4{0u, 0u, 0u, 0u} : ld16<YNT>(yrow[i] + (int64_t)colc * ESZ + 16 * q);
     }
 
     __device__ inline void compute_store(int c, const typename Tile::B &b, const YBuf &y) const
@@ -76,8 +78,8 @@ struct ExpandWave {
                     o1[q] = __float_as_uint(__uint_as_float(y.r[i][NY - 1][q]) + acc[4 + q][i]);
                 }
                 if (ok) {
-                    st16<false>(yp, o0);
-                    st16<false>(yp + 16, o1);
+                    st16<YNT>(yp, o0);
+                    st16<YNT>(yp + 16, o1);
                 }
             } else {
                 u32x4 o;
@@ -88,7 +90,7 @@ struct ExpandWave {
                     const float f1 = __uint_as_float(u & 0xFFFF0000u) + acc[2 * q + 1][i];
                     o[q] = pack_bf16_rne(f0, f1);
                 }
-                if (ok) st16<false>(yp, o);
+                if (ok) st16<YNT>(yp, o);
             }
         }
     }
@@ -131,14 +133,14 @@ struct ExpandWave {
 // already sits in LDS as [16][R] floats (the kernel that runs shrink and expand in one launch).
 // perm_lds: null = the sorted order comes from p.perm; otherwise from LDS (the kernel that also
 // builds the segments).
-template <int R, bool F32, int NI, bool OVW>
+template <int R, bool F32, int NI, bool OVW, bool YNT = false>
 __device__ inline void expand_item(const ExpandParams &p, const lora_tile &t, const Unit &unit, int pj,
                                    int c0, int c1, int lane, const float *vlds = nullptr,
                                    const uint16_t *perm_lds = nullptr)
 {
     using Tile = ExpandTile<R>;
     constexpr int KS = Tile::KS, KV = Tile::KV, ESZ = F32 ? 4 : 2;
-    ExpandWave<R, F32, NI, OVW> w;
+    ExpandWave<R, F32, NI, OVW, YNT> w;
     w.lane = lane;
     w.g = lane >> 4;
     w.i16 = lane & 15;
@@ -191,7 +193,7 @@ __device__ inline void expand_item(const ExpandParams &p, const lora_tile &t, co
                     for (int q = 0; q < 4; ++q) s[ks][4 * h + q] += in ? buf[u][ks][h][q] : 0.f;
         }
     };
-    typename ExpandWave<R, F32, NI, OVW>::Stage st[ExpandWave<R, F32, NI, OVW>::D];
+    typename ExpandWave<R, F32, NI, OVW, YNT>::Stage st[ExpandWave<R, F32, NI, OVW, YNT>::D];
     if (vlds) {                                                  // wave-uniform
         w.prefetch(c0, c1, st);
 #pragma unroll
@@ -238,16 +240,16 @@ __device__ inline void expand_item(const ExpandParams &p, const lora_tile &t, co
 
 // one wave, one tile, chunks [c0, c1) of projection pj; the specialisation on the number of row
 // quads is picked here (wave-uniform)
-template <int R, bool F32, bool OVW>
+template <int R, bool F32, bool OVW, bool YNT = false>
 __device__ inline void expand_tile_chunks(const ExpandParams &p, const lora_tile &t, const Unit &unit,
                                           int pj, int c0, int c1, int lane, const float *vlds = nullptr,
                                           const uint16_t *perm_lds = nullptr)
 {
     switch ((t.n_rows + 3) >> 2) {
-    case 1: expand_item<R, F32, 1, OVW>(p, t, unit, pj, c0, c1, lane, vlds, perm_lds); break;
-    case 2: expand_item<R, F32, 2, OVW>(p, t, unit, pj, c0, c1, lane, vlds, perm_lds); break;
-    case 3: expand_item<R, F32, 3, OVW>(p, t, unit, pj, c0, c1, lane, vlds, perm_lds); break;
-    default: expand_item<R, F32, 4, OVW>(p, t, unit, pj, c0, c1, lane, vlds, perm_lds); break;
+    case 1: expand_item<R, F32, 1, OVW, YNT>(p, t, unit, pj, c0, c1, lane, vlds, perm_lds); break;
+    case 2: expand_item<R, F32, 2, OVW, YNT>(p, t, unit, pj, c0, c1, lane, vlds, perm_lds); break;
+    case 3: expand_item<R, F32, 3, OVW, YNT>(p, t, unit, pj, c0, c1, lane, vlds, perm_lds); break;
+    default: expand_item<R, F32, 4, OVW, YNT>(p, t, unit, pj, c0, c1, lane, vlds, perm_lds); break;
     }
 }
 

@@ -36,6 +36,11 @@ constexpr int kFusedMaxChunks = 64;    // widest group, in 128-column chunks per
 constexpr int kFusedMaxTiles = 64;     // largest batch, as the host's upper bound of the tile count
 constexpr int kFusedMinChunks = 16;    // 128-column chunks a workgroup expands at least
 constexpr int kFusedWorkgroups = 1024; // workgroups aimed at
+// Cache hints of the activation streams of the decode kernels, measured on MI355X with the Mixtral
+// shapes (512 to 2900 tokens, top-2): input rows that are read once are streamed from 64 MiB on
+// (a quarter of the 256 MiB memory-side cache), the output rows of one call from 256 MiB on.
+constexpr int kStreamXMiB = 64;
+constexpr int kStreamYMiB = 256;
 constexpr int kMaxFused = 3;         // projections that share an input in one launch (q/k/v, gate/up)
 
 // ---- packed layout sizes ---------------------------------------------------------------
@@ -115,6 +120,7 @@ struct ShrinkParams {
     int grid;
     int wave_per_tile;       // decode kernel: every wave takes a whole tile (no K split across waves)
     int build;               // decode kernel: the segments are built inside the launch, from `seg`
+    int x_stream;            // decode kernel, K-split form: x rows loaded with the streaming hint
     SegParams seg;
 };
 
@@ -142,6 +148,7 @@ struct ExpandParams {
     int tile_group;          // decode kernel: consecutive wave items walk over this many tiles
     int out_f32;
     int overwrite;           // decode kernel, bf16 output: write the update, do not read the rows
+    int y_stream;            // decode kernel: output rows read and written with the streaming hint
     int rank;
     int grid;
 };

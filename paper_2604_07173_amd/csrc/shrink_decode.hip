@@ -32,15 +32,18 @@ namespace {
 // BUILD: the segments are not there yet; every workgroup sorts the batch for itself in LDS
 // first (segments_inline.h) and takes tile records and row indices from there, and workgroup 0
 // writes them out for the launches that follow.
-template <int R, int NPROJ, bool NT, bool WPT, bool BUILD = false>
+//
+// XNT: the x rows are loaded with the streaming hint (K-split form only).
+template <int R, int NPROJ, bool NT, bool WPT, bool BUILD = false, bool XNT = false>
 __global__ __launch_bounds__(256, 2) void shrink16_kernel(ShrinkParams p,
                                                           const lora_tile *__restrict__ tiles,
                                                           const Unit *__restrict__ units,
                                                           const int32_t *__restrict__ counts)
 {
-    using Wave = ShrinkWave<R, NPROJ, NT>;
+    using Wave = ShrinkWave<R, NPROJ, NT, XNT>;
     constexpr int NACC = Wave::NACC, KU = Wave::KU;
     static_assert(!(BUILD && WPT), "the build needs the whole workgroup");
+    static_assert(!(XNT && (BUILD || WPT)), "streamed x rows: K-split form without the build only");
     union Scratch {                   // the build's counts are dead before the first sums are added
         f32x4 red[WPT ? 1 : 4][NPROJ][NACC][WPT ? 1 : 64];
         std::conditional_t<BUILD, InlineCounts, char> counts;
@@ -158,6 +161,9 @@ hipError_t launch_rn(const ShrinkParams &p, hipStream_t s)
                            p.tiles, p.units, p.counts);
     } else if (p.wave_per_tile)
         hipLaunchKernelGGL((shrink16_kernel<R, NPROJ, true, true>), dim3(p.grid), dim3(256), 0, s, p,
+                           p.tiles, p.units, p.counts);
+    else if (p.x_stream)
+        hipLaunchKernelGGL((shrink16_kernel<R, NPROJ, true, false, false, true>), dim3(p.grid), dim3(256), 0, s, p,
                            p.tiles, p.units, p.counts);
     else
         hipLaunchKernelGGL((shrink16_kernel<R, NPROJ, true, false>), dim3(p.grid), dim3(256), 0, s, p,

@@ -18,7 +18,9 @@
 
 namespace lora {
 
-template <int R, int NPROJ, bool NT>
+// NT: the packed A is loaded with the streaming hint (it is read once).  XNT: so are the x rows
+// (for inputs too large to stay in a cache until anyone reads them again).
+template <int R, int NPROJ, bool NT, bool XNT = false>
 struct ShrinkWave {
     static constexpr int NB = R >= 16 ? R / 16 : 1;            // weight tiles per K unit
     static constexpr int XN = R == 8 ? 2 : 1;                  // x operands per K unit
@@ -58,7 +60,7 @@ struct ShrinkWave {
             for (int h = 0; h < XN; ++h) {
                 const int c = kb * KU + h * 32 + g * 8;
                 const bool c_ok = c < h_in;
-                const u32x4 t = ld16<false>(xp + (c_ok ? c : 0));
+                const u32x4 t = ld16<XNT>(xp + (c_ok ? c : 0));
                 s.x[u][h] = (k_ok && row_ok && c_ok) ? t : zero4;
             }
         }

@@ -39,6 +39,12 @@ def test_every_declared_symbol_is_exported(lib):
     assert sorted(L.EXPORTED_SYMBOLS) == names
 
 
+def test_activation_policy_calls_reject_a_missing_pool(lib):
+    assert lib.lora_pool_set_activation_policy(None, L.LORA_ACT_STREAMING) == -5
+    assert lib.lora_pool_activation_policy(None) == -5
+    assert (L.LORA_ACT_AUTO, L.LORA_ACT_RESIDENT, L.LORA_ACT_STREAMING) == (0, 1, 2)
+
+
 def test_strerror(lib):
     assert L.lora_strerror(0) == "ok"
     assert "rank" in L.lora_strerror(-3)
