@@ -22,7 +22,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
-COLD_SETS = 8           # copies of the activation buffers of the cold-activation measurement
+COLD_SETS = 24          # copies of the activation buffers of the cold-activation measurement (2.5 GB for the Mixtral batch)
 
 
 def parse_args():
