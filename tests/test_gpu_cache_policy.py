@@ -134,3 +134,27 @@ def test_rows_beyond_the_thresholds_are_streamed_by_default():
     check_delta(W.bf16_bits_to_f32(got).astype(np.float64), res.delta, "streamed by default")
     del dp, db, out
     torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("name", ["dense_small", "llama8b_decode", "mixtral_moe_decode", "finegrained_moe_decode"])
+def test_full_size_workloads_are_bit_identical_under_the_streaming_policy(name):
+    """The decode workloads at their full sizes, as the benchmark's cold-activation measurement
+    runs them: LORA_ACT_STREAMING against the default policy, every output row bit for bit (the
+    default policy's outputs are compared with the oracle in test_gpu_configs.py)."""
+    w = W.WORKLOADS[name]
+    b = W.make_batch(w, 1234, y_mode="normal")
+    ws = W.make_weights(w, 1234, n_layers=1)
+    dp, db = DevicePool(ws, b.scale), DeviceBatch(b)
+    run = LayerRunner(dp, db)
+    out = {}
+    for policy in (L.LORA_ACT_AUTO, L.LORA_ACT_STREAMING):
+        L.lora_pool_set_activation_policy(dp.pool, policy)
+        db.reset_y()
+        run.step(0)
+        torch.cuda.synchronize()
+        out[policy] = {p.name: db.y[p.name].clone() for p in w.projs}
+    for p in w.projs:
+        assert torch.equal(out[L.LORA_ACT_AUTO][p.name], out[L.LORA_ACT_STREAMING][p.name]), p.name
+        assert not torch.equal(out[L.LORA_ACT_AUTO][p.name], to_dev(b.y_in[p.name])), p.name
+    del dp, db, out
+    torch.cuda.empty_cache()
