@@ -208,12 +208,12 @@ int pick_tile_rows(const lora_pool *p, int P)
     if (p->d.rank == 8) return kDecodeTileRows;      // the 32-row shrink has no rank-8 form
     static const int forced = env_int("LORA_TILE_ROWS", 0, 0, 32);
     if (forced == kTileRows || forced == kDecodeTileRows) return forced;
-    // Measured crossover on the Mixtral shapes at rank 16: about 22 rows per key, provided the batch
+    // Measured crossover on the Mixtral shapes at rank 16: about 32 rows per key, provided the batch
     // is long enough for the long-segment kernels' work items (128 rows) to fill the chip; a
     // batch of 4032 rows over 64 keys (llama shapes) is still faster with 16-row tiles.
     const int64_t keys = (int64_t)p->d.n_adapters * p->d.n_experts;
     if ((int64_t)P >= 64 * keys) return kTileRows;
-    return ((int64_t)P >= 24 * keys && P >= 6144) ? kTileRows : kDecodeTileRows;
+    return ((int64_t)P >= 32 * keys && P >= 8192) ? kTileRows : kDecodeTileRows;
 }
 
 struct KSplit {

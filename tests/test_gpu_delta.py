@@ -243,11 +243,11 @@ def test_long_segment_kernels_at_ragged_widths(rank, h_in, h_out, y_mode):
     assert np.array_equal(got[none], b.y_in["p"][none])
 
 
-@pytest.mark.parametrize("tokens,tile_rows", [(6143, 16), (6144, 32), (2048, 16)])
+@pytest.mark.parametrize("tokens,tile_rows", [(8191, 16), (8192, 32), (2048, 16)])
 def test_kernel_family_switch_for_long_decode_batches(tokens, tile_rows):
-    """Between 24 and 64 rows per key the 32-row-tile kernels are taken only from 6144 rows on:
-    both sides of that limit, 128 keys, against the oracle (all rows)."""
-    w = W.Workload("t", "dense", 128, 1, 1, 16, (W.Proj("p", 264, 136, "x"),), tokens, "zipf", 0.6)
+    """Between 32 and 64 rows per key the 32-row-tile kernels are taken only from 8192 rows on:
+    both sides of that limit, 200 keys, against the oracle (all rows)."""
+    w = W.Workload("t", "dense", 200, 1, 1, 16, (W.Proj("p", 264, 136, "x"),), tokens, "zipf", 0.6)
     b, ws, got, (dp, db, run) = run_dense(w, 52, "zero", drop=0.02)
     assert db.seg.c.tile_rows == tile_rows
     res = oracle_projection(b, ws, 0, 0)
