@@ -206,14 +206,17 @@ int64_t tiles_upper_bound(const lora_pool *p, int P, int tile_rows)
 int pick_tile_rows(const lora_pool *p, int P)
 {
     if (p->d.rank == 8) return kDecodeTileRows;      // the 32-row shrink has no rank-8 form
-    static const int forced = env_int("LORA_TILE_ROWS", 0, 0, 32);
+    // test switch, looked at on every call: segments remember the height they were built with and
+    // every compute call checks it, so a change between two calls is an error, not a mismatch
+    const int forced = env_int("LORA_TILE_ROWS", 0, 0, 32);
     if (forced == kTileRows || forced == kDecodeTileRows) return forced;
-    // Measured crossover on the Mixtral shapes at rank 16: about 32 rows per key, provided the batch
-    // is long enough for the long-segment kernels' work items (128 rows) to fill the chip; a
-    // batch of 4032 rows over 64 keys (llama shapes) is still faster with 16-row tiles.
+    // Measured crossovers on MI355X: Mixtral shapes at rank 16 (256 keys) at 8192 rows, llama shapes
+    // at rank 16 (64 keys) between 8192 and 16384 rows, prefill shapes at rank 64 (8 keys) between
+    // 1024 and 2048 rows: the long-segment kernels pay off from rows x rank = 2^17 on (their two
+    // extra launches and 128-row work items need that much to amortise), if the segments are
+    // long enough to fill 32-row tiles at all.
     const int64_t keys = (int64_t)p->d.n_adapters * p->d.n_experts;
-    if ((int64_t)P >= 64 * keys) return kTileRows;
-    return ((int64_t)P >= 32 * keys && P >= 8192) ? kTileRows : kDecodeTileRows;
+    return ((int64_t)P >= 32 * keys && (int64_t)P * p->d.rank >= kLongMinRowsTimesRank) ? kTileRows : kDecodeTileRows;
 }
 
 struct KSplit {

@@ -39,6 +39,7 @@ constexpr int kFusedWorkgroups = 1024; // workgroups aimed at
 // Cache hints of the activation streams of the decode kernels, measured on MI355X with the Mixtral
 // shapes (512 to 2900 tokens, top-2): input rows that are read once are streamed from 64 MiB on
 // (a quarter of the 256 MiB memory-side cache), the output rows of one call from 256 MiB on.
+constexpr int kLongMinRowsTimesRank = 1 << 17;   // long-segment kernels from this many rows x rank on
 constexpr int kStreamXMiB = 64;
 constexpr int kStreamYMiB = 256;
 constexpr int kMaxFused = 3;         // projections that share an input in one launch (q/k/v, gate/up)

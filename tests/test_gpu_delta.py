@@ -98,9 +98,13 @@ def test_f32_accumulate_keeps_base():
     assert np.array_equal(got[none], W.bf16_bits_to_f32(b.y_in["p"][none]).astype(np.float64))
 
 
+@pytest.mark.parametrize("forced", ["", "32"], ids=["family by size", "32-row tiles"])
 @pytest.mark.parametrize("tokens", [1, 15, 16, 17, 31, 32, 33, 64, 65, 130])
-def test_segment_lengths_around_tile_boundaries(tokens):
-    """One adapter only: the segment has exactly `tokens` rows (1 .. several 32-row tiles)."""
+def test_segment_lengths_around_tile_boundaries(tokens, forced, monkeypatch):
+    """One adapter only: the segment has exactly `tokens` rows (1 .. several 32-row tiles), with the
+    kernels the library picks for so few rows and with the long-segment kernels forced."""
+    if forced:
+        monkeypatch.setenv("LORA_TILE_ROWS", forced)
     w = dense_workload(16, 264, 392, n=1, tokens=tokens)
     b, ws, got, _ = run_dense(w, 15, "normal")
     res = oracle_projection(b, ws, 0, 0)
@@ -178,9 +182,12 @@ def test_apply_is_bit_identical_to_shrink_then_expand(rank, h_in, h_out, n, toke
 
 @pytest.mark.parametrize("rank", [8, 16, 32, 64])
 @pytest.mark.parametrize("tokens,n", [(70, 5), (2100, 3)])      # decode tiles / long segments
-def test_group_of_three_projections_matches_single_calls(rank, tokens, n):
+def test_group_of_three_projections_matches_single_calls(rank, tokens, n, monkeypatch):
     """q/k/v-like group: same input, widths 392 / 136 / 136; bit-identical to per-projection
-    lora_apply calls and within tolerance of the oracle."""
+    lora_apply calls and within tolerance of the oracle.  The long batch runs on the long-segment
+    kernels (forced: the library takes them from rows x rank = 2^17 on)."""
+    if tokens == 2100:
+        monkeypatch.setenv("LORA_TILE_ROWS", "32")
     projs = (W.Proj("q", 264, 392, "x"), W.Proj("k", 264, 136, "x"), W.Proj("v", 264, 136, "x"))
     w = W.Workload("t", "dense", n, 1, 1, rank, projs, tokens, "uniform", 0.0)
     b = W.make_batch(w, 41, y_mode="normal", no_adapter_frac=0.1, hetero_scale=True)
@@ -209,10 +216,11 @@ def test_group_of_three_projections_matches_single_calls(rank, tokens, n):
 
 @pytest.mark.parametrize("y_mode", ["zero", "normal"])
 @pytest.mark.parametrize("rank", [16, 64])
-def test_long_segment_kernels_with_many_short_segments(rank, y_mode):
-    """P >= 64 * n_keys selects the 32-row-tile kernels; a Zipf draw over 24 adapters then
+def test_long_segment_kernels_with_many_short_segments(rank, y_mode, monkeypatch):
+    """The 32-row-tile kernels (forced for this small batch) on a Zipf draw over 24 adapters that
     leaves many segments of a few rows next to long ones, so most four-tile groups of the
     shrink straddle a segment boundary and the expand reloads B inside its tile groups."""
+    monkeypatch.setenv("LORA_TILE_ROWS", "32")
     w = W.Workload("t", "dense", 24, 1, 1, rank, (W.Proj("p", 328, 264, "x"),), 2048, "zipf", 1.3)
     b, ws, got, (dp, db, run) = run_dense(w, 51, y_mode, drop=0.05)
     assert db.seg.c.tile_rows == 32
@@ -227,10 +235,11 @@ def test_long_segment_kernels_with_many_short_segments(rank, y_mode):
 
 @pytest.mark.parametrize("y_mode", ["zero", "normal"])
 @pytest.mark.parametrize("rank,h_in,h_out", [(16, 40, 8), (64, 72, 136), (32, 264, 520), (16, 136, 1032), (64, 2056, 72)])
-def test_long_segment_kernels_at_ragged_widths(rank, h_in, h_out, y_mode):
-    """The 32-row-tile kernels at widths that are not whole stages of 128 K values nor whole
-    chunks of 128 columns (the shrink fetches x a stage of whole lines at a time): 3 adapters,
-    400 rows, every row against the oracle."""
+def test_long_segment_kernels_at_ragged_widths(rank, h_in, h_out, y_mode, monkeypatch):
+    """The 32-row-tile kernels (forced for this small batch) at widths that are not whole stages of
+    128 K values nor whole chunks of 128 columns (the shrink fetches x a stage of whole lines at a
+    time): 3 adapters, 400 rows, every row against the oracle."""
+    monkeypatch.setenv("LORA_TILE_ROWS", "32")
     w = dense_workload(rank, h_in, h_out, n=3, tokens=400)
     b, ws, got, (dp, db, run) = run_dense(w, 53, y_mode, drop=0.03)
     assert db.seg.c.tile_rows == 32
@@ -243,20 +252,25 @@ def test_long_segment_kernels_at_ragged_widths(rank, h_in, h_out, y_mode):
     assert np.array_equal(got[none], b.y_in["p"][none])
 
 
-@pytest.mark.parametrize("tokens,tile_rows", [(8191, 16), (8192, 32), (2048, 16)])
-def test_kernel_family_switch_for_long_decode_batches(tokens, tile_rows):
-    """Between 32 and 64 rows per key the 32-row-tile kernels are taken only from 8192 rows on:
-    both sides of that limit, 200 keys, against the oracle (all rows)."""
-    w = W.Workload("t", "dense", 200, 1, 1, 16, (W.Proj("p", 264, 136, "x"),), tokens, "zipf", 0.6)
+@pytest.mark.parametrize("rank,n,tokens,tile_rows", [(16, 200, 8191, 16), (16, 200, 8192, 32), (16, 200, 2048, 16),
+                                                     (64, 8, 2047, 16), (64, 8, 2048, 32), (16, 64, 4096, 16),
+                                                     (32, 300, 8192, 16)])
+def test_kernel_family_switch_for_long_decode_batches(rank, n, tokens, tile_rows):
+    """The 32-row-tile kernels are taken from rows x rank = 2^17 on (8192 rows at rank 16, 2048 at
+    rank 64) if there are at least 32 rows per key: both sides of the limits, against the oracle
+    (all rows)."""
+    w = W.Workload("t", "dense", n, 1, 1, rank, (W.Proj("p", 264, 136, "x"),), tokens, "zipf", 0.6)
     b, ws, got, (dp, db, run) = run_dense(w, 52, "zero", drop=0.02)
     assert db.seg.c.tile_rows == tile_rows
     res = oracle_projection(b, ws, 0, 0)
-    check_delta(W.bf16_bits_to_f32(got).astype(np.float64), res.delta, f"family switch {tokens}")
+    check_delta(W.bf16_bits_to_f32(got).astype(np.float64), res.delta, f"family switch r{rank} {n} keys {tokens}")
 
 
-@pytest.mark.parametrize("tokens", [1, 40, 5000])
-def test_batch_without_any_adapter_leaves_everything_untouched(tokens):
+@pytest.mark.parametrize("tokens,forced", [(1, ""), (40, ""), (5000, ""), (5000, "32")])
+def test_batch_without_any_adapter_leaves_everything_untouched(tokens, forced, monkeypatch):
     """Every row has id -1: no segment, no tile; y keeps its bits (both kernel families)."""
+    if forced:
+        monkeypatch.setenv("LORA_TILE_ROWS", forced)
     w = dense_workload(16, 200, 136, n=3, tokens=tokens)
     b = W.make_batch(w, 61, y_mode="normal")
     b.adapter_id[:] = -1

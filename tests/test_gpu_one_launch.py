@@ -140,14 +140,15 @@ def test_one_launch_is_bit_identical_run_to_run_and_in_a_graph():
     check_accumulate(bits_from_dev(db.y["p"]), oracle_projection(b, ws, 0, 0), "one launch in a graph")
 
 
-def test_f32_output_and_long_segments_take_two_or_more_launches():
+def test_f32_output_and_long_segments_take_two_or_more_launches(monkeypatch):
     w = W.Workload("t", "dense", 2, 1, 1, 16, (W.Proj("p", 264, 392, "x"),), 40, "uniform", 0.0)
     b = W.make_batch(w, 17)
     dp, db = DevicePool(W.make_weights(w, 17, bank_elems=1 << 20), b.scale), DeviceBatch(b)
     LayerRunner(dp, db).build_segments()
     assert L.lora_group_launches(dp.pool, 0, 1, db.P, db.seg) == 1
     assert L.lora_group_launches(dp.pool, 0, 1, db.P, db.seg, L.LORA_DTYPE_F32) == 2
-    w2 = W.scaled(w, tokens=400)                      # 200 rows per adapter: 32-row tiles
+    monkeypatch.setenv("LORA_TILE_ROWS", "32")        # the long-segment kernels, forced for so few rows
+    w2 = W.scaled(w, tokens=400)
     b2 = W.make_batch(w2, 17)
     db2 = DeviceBatch(b2)
     LayerRunner(dp, db2).build_segments()
