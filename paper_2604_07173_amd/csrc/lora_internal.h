@@ -121,7 +121,7 @@ struct ShrinkParams {
     int grid;
     int wave_per_tile;       // decode kernel: every wave takes a whole tile (no K split across waves)
     int build;               // decode kernel: the segments are built inside the launch, from `seg`
-    int x_stream;            // decode kernel, K-split form: x rows loaded with the streaming hint
+    int x_stream;            // decode kernel, K-split form: x rows loaded with the streaming hint (ranks 8, 16: as whole lines)
     SegParams seg;
 };
 

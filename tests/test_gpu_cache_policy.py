@@ -158,3 +158,33 @@ def test_full_size_workloads_are_bit_identical_under_the_streaming_policy(name):
         assert not torch.equal(out[L.LORA_ACT_AUTO][p.name], to_dev(b.y_in[p.name])), p.name
     del dp, db, out
     torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("rank,n_proj", [(8, 1), (16, 2), (16, 3), (32, 1)])
+def test_streamed_inputs_at_a_ragged_width(rank, n_proj):
+    """2100 rows of 16392 inputs (65.7 MiB, read once: streamed, at ranks 8 and 16 as whole cache
+    lines through LDS) over 150 adapters, groups of one to three projections of 136 to 264 outputs;
+    the width is not a whole number of 128-value steps and the tiles are ragged.  Every row against
+    the oracle, and bit-identical to the resident policy (plain loads in operand layout)."""
+    projs = tuple(W.Proj(f"p{j}", 16392, 136 + 64 * j, "x") for j in range(n_proj))
+    w = W.Workload("t", "dense", 150, 1, 1, rank, projs, 2100, "zipf", 0.7)
+    assert w.pairs * 16392 * 2 >= 64 << 20
+    b = W.make_batch(w, 21, y_mode="zero", no_adapter_frac=0.03, hetero_scale=True)
+    ws = W.make_weights(w, 21, bank_elems=1 << 22)
+    dp, db = DevicePool(ws, b.scale), DeviceBatch(b)
+    run = LayerRunner(dp, db)
+    out = {}
+    for policy in (L.LORA_ACT_AUTO, L.LORA_ACT_RESIDENT):
+        L.lora_pool_set_activation_policy(dp.pool, policy)
+        db.reset_y()
+        run.step(0, one_call=False)
+        torch.cuda.synchronize()
+        assert db.seg.c.tile_rows == 16
+        out[policy] = {p.name: bits_from_dev(db.y[p.name]).copy() for p in projs}
+    for j, p in enumerate(projs):
+        assert np.array_equal(out[L.LORA_ACT_AUTO][p.name], out[L.LORA_ACT_RESIDENT][p.name]), p.name
+        res = oracle_projection(b, ws, 0, j)
+        check_delta(W.bf16_bits_to_f32(out[L.LORA_ACT_AUTO][p.name]).astype(np.float64), res.delta,
+                    f"streamed ragged inputs r{rank}/{p.name}")
+    del dp, db
+    torch.cuda.empty_cache()
