@@ -11,7 +11,7 @@ CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "liblora.so")
 SOURCES = ["api.hip", "pack.hip", "segments.hip", "segments_large.hip", "shrink.hip", "expand.hip",
            "shrink_decode.hip", "expand_decode.hip", "fused_decode.hip", "combine.hip", "provision.cpp"]
-HEADERS = ["lora_internal.h", "lora_layout.h", "lora_device.h", "expand_common.h", "expand_item.h", "shrink_wave.h", "segments_common.h", os.path.join("..", "..", "include", "lora.h"),
+HEADERS = ["lora_internal.h", "lora_layout.h", "lora_device.h", "expand_common.h", "expand_item.h", "shrink_wave.h", "segments_common.h", "segments_inline.h", os.path.join("..", "..", "include", "lora.h"),
            os.path.join("..", "..", "include", "lora_provision.h")]
 
 HIPCC_FLAGS = [
