@@ -55,7 +55,7 @@ enum {
 enum {
     LORA_ACT_AUTO = 0,       /* in a cache unless a call's rows are too many to be (default) */
     LORA_ACT_RESIDENT = 1,   /* always in a cache: no streaming hints on activations */
-    LORA_ACT_STREAMING = 2   /* in HBM only: output rows are read and written with streaming hints */
+    LORA_ACT_STREAMING = 2   /* in HBM only: activations are read and written with streaming hints */
 };
 
 /* bits of the device status word written by lora_build_segments */
@@ -174,7 +174,7 @@ int lora_pool_set_adapter(lora_pool *pool, int adapter, int rank, float scale, v
  *   LORA_ACT_RESIDENT        no streaming hint on any activation, whatever its size.
  *   LORA_ACT_STREAMING       for callers whose activations are in HBM only when a call starts
  *       (arrived over a link, or written long ago): output rows are read and written with
- *       streaming hints at every size; input rows as under LORA_ACT_AUTO.
+ *       streaming hints at every size, and so are input rows that every pair reads for itself.
  * Results are bit-identical under all three; only the decode kernels (tiles of at most 16 rows)
  * look at the policy, the long-segment kernels always stream their outputs.  Host state only:
  * takes effect from the next call on, must not race with calls on the same pool.  Errors:

@@ -313,13 +313,15 @@ size_t parts_bytes(const lora_pool *pool, int n_parts, int P)
 // x rows that every pair reads for itself (no gather through src_row) are read exactly once, so
 // keeping them cacheable pays only while they are small against the memory-side cache: a quarter
 // of it and more is streamed, so that it does not push out the output rows, which are read,
-// written and read again by whatever runs next.  Output rows are streamed when the caller says
-// its activations are not in a cache when a call starts (LORA_ACT_STREAMING), or when one call's
-// outputs exceed the memory-side cache anyway.  LORA_ACT_RESIDENT switches both off.
+// written and read again by whatever runs next.  Output rows, and read-once input rows of any
+// size, are streamed when the caller says its activations are not in a cache when a call starts
+// (LORA_ACT_STREAMING); output rows also when one call's outputs exceed the memory-side cache
+// anyway.  LORA_ACT_RESIDENT switches both off.
 bool stream_x(const lora_pool *pool, const int32_t *src_row, int64_t x_bytes)
 {
     static const int mb = tune_int("LORA_X_STREAM_MB", kStreamXMiB, 1, 1 << 20);
     if (pool->act_policy == LORA_ACT_RESIDENT || src_row) return false;
+    if (pool->act_policy == LORA_ACT_STREAMING) return true;
     return x_bytes >= (int64_t)mb << 20;
 }
 
